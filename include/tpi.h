@@ -1,0 +1,204 @@
+/*
+ * libtpi -- MI355X (gfx950) hot path of TPI-LLM tensor-parallel inference
+ * (arxiv 2410.00531): one device's shard of a Llama-style decoder layer, the
+ * star all-reduce sum of the N shards' partial outputs, and a sliding window
+ * of layer shards streamed from pinned host memory into HBM.
+ *
+ * Conventions for every entry point
+ *   - C ABI, plain pointers and sizes.  A pointer is a DEVICE pointer unless
+ *     its name starts with host_ or its comment says "host".
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     Compute entry points only enqueue work on that stream and return; they
+ *     never synchronise, allocate or free.
+ *   - The caller owns every buffer (weights, KV cache, activations,
+ *     workspace, pinned host blobs, window slots).  The library owns only
+ *     tpi_window objects.
+ *   - Return value: TPI_OK (0) or a negative tpi_status.  Argument errors are
+ *     detected before anything is queued; tpi_last_error() returns a
+ *     thread-local description of the last failure.
+ *   - Weight matrices are row-major [out][in], so y = W x reads rows of W.
+ *   - Alignment: every device pointer 16-byte aligned; hidden, ffn_local and
+ *     head_dim multiples of 4 (TPI_EUNSUPPORTED otherwise).
+ */
+#ifndef TPI_H
+#define TPI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TPI_OK = 0,
+    TPI_EINVAL = -1,        /* null pointer, size or position out of range, unknown enum   */
+    TPI_EUNSUPPORTED = -2,  /* valid request that this build has no kernel for             */
+    TPI_ERUNTIME = -3,      /* a HIP call failed; text in tpi_last_error()                 */
+    TPI_ESTATE = -4         /* window protocol violated (acquire before prefetch, ...)     */
+} tpi_status;
+
+enum { TPI_F32 = 0, TPI_BF16 = 1 };
+
+/* The all-reduce sits between the two phases of a layer (Alg. 1 / Alg. 2 loop
+ * body: attention, allreduce, FFN, allreduce). */
+enum { TPI_PHASE_ATTN = 1, TPI_PHASE_FFN = 2 };
+
+/* Upper limits of this build. */
+#define TPI_MAX_REDUCE_RANKS 64   /* partial vectors one tpi_star_reduce call can sum   */
+#define TPI_MAX_HEAD_DIM 256
+#define TPI_ATTN_MAX_SPLITS 32    /* KV-length splits of the decode attention            */
+#define TPI_MAX_BATCH_SHARDS 16   /* shards one batched call can take                    */
+
+/* Shape of ONE device's shard of one decoder layer (Sec. 3.1 Step 1: attention
+ * heads and FFN columns are divided among devices). */
+typedef struct tpi_shard_cfg {
+    int32_t hidden;       /* h: hidden size, replicated on every device             */
+    int32_t n_q_local;    /* query heads on this device                             */
+    int32_t n_kv_local;   /* KV heads on this device; must divide n_q_local         */
+    int32_t head_dim;     /* d                                                      */
+    int32_t ffn_local;    /* FFN columns on this device                             */
+    int32_t max_seq;      /* slots per KV head in the cache                         */
+    float   rms_eps;      /* RMSNorm epsilon (inside the square root)               */
+    float   rope_base;    /* rotary base; theta_i = base^(-2i/d), rotate-half pairs */
+    int32_t dtype;        /* TPI_F32 (decode) or TPI_BF16 (prefill weights/inputs)  */
+} tpi_shard_cfg;
+
+/* Weights of one layer of one shard: the attention block (norm gain, W_Q, W_K,
+ * W_V, W_O slices) and the FFN block (norm gain, gate, up, down slices) of the
+ * appendix parameter-count table.  Element type is cfg.dtype except the two
+ * gains, which are always fp32. */
+typedef struct tpi_layer_weights {
+    const void *attn_norm;  /* [h] fp32                                               */
+    const void *w_qkv;      /* [(n_q+2 n_kv) d][h]: Q-head rows, then K, then V rows  */
+    const void *w_o;        /* [h][n_q d]   (row-parallel: yields a partial sum)      */
+    const void *ffn_norm;   /* [h] fp32                                               */
+    const void *w_gate;     /* [ffn_local][h]                                         */
+    const void *w_up;       /* [ffn_local][h]                                         */
+    const void *w_down;     /* [h][ffn_local] (row-parallel: yields a partial sum)    */
+} tpi_layer_weights;
+
+/* This device's KV cache of one layer: only its own heads (Sec. 3.1, the
+ * distributed KV cache).  [n_kv_local][max_seq][head_dim], element type
+ * cfg.dtype.  K is stored after rotation, V as projected. */
+typedef struct tpi_kv_layer {
+    void *k;
+    void *v;
+} tpi_kv_layer;
+
+/* Bytes of workspace a decode (n_tokens = 1) or prefill call needs.  The
+ * workspace carries no state between calls, needs no initialisation, and may
+ * be shared by calls on the same stream.  Returns 0 on a bad cfg. */
+size_t tpi_workspace_bytes(const tpi_shard_cfg *cfg, int32_t n_tokens);
+
+/*
+ * One phase of one layer for one shard, one token (batch 1 decode), fp32.
+ *
+ * TPI_PHASE_ATTN -- the term inside all_reduce() of Eq. 1:
+ *   xn = rmsnorm(h_in, attn_norm); q,k,v = W_qkv xn; rotate q and k at `pos`;
+ *   store k,v in cache slot `pos` (exactly that slot, nothing else in the
+ *   cache is written); softmax(q K^T / sqrt(d)) V over slots 0..pos for each
+ *   local head (query head j uses KV head j / (n_q_local / n_kv_local));
+ *   partial_out = W_o o.
+ * TPI_PHASE_FFN -- the term inside all_reduce() of Eq. 2:
+ *   xn = rmsnorm(h_in, ffn_norm);
+ *   partial_out = W_down (silu(W_gate xn) * (W_up xn)).
+ *
+ * h_in [h] fp32: H_ffn of the previous layer (ATTN) or H_attn (FFN).
+ * partial_out [h] fp32.  kv may be NULL for TPI_PHASE_FFN.
+ * Errors: TPI_EINVAL for null pointers, pos < 0, pos >= max_seq, odd or
+ * non-positive sizes, n_q_local % n_kv_local != 0, unknown phase;
+ * TPI_EUNSUPPORTED for cfg.dtype != TPI_F32 or sizes outside the limits above.
+ */
+int tpi_shard_layer_decode(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w,
+                           const tpi_kv_layer *host_kv, int32_t pos, int phase,
+                           const float *h_in, float *partial_out, void *workspace,
+                           void *stream);
+
+/*
+ * The same phase for n_shards emulated devices in one set of launches (the
+ * shards of a layer are independent between all-reduces, Sec. 3.1 Step 3).
+ * host_w, host_kv, host_partial_out and host_workspace are HOST arrays of
+ * n_shards entries; all shards share cfg, pos and h_in.  Results are
+ * identical to n_shards calls of tpi_shard_layer_decode.
+ * 1 <= n_shards <= TPI_MAX_BATCH_SHARDS.
+ */
+int tpi_shards_layer_decode(const tpi_shard_cfg *cfg, int32_t n_shards,
+                            const tpi_layer_weights *host_w, const tpi_kv_layer *host_kv,
+                            int32_t pos, int phase, const float *h_in,
+                            float *const *host_partial_out, void *const *host_workspace,
+                            void *stream);
+
+/*
+ * Prefill: the same two phases for n_tokens consecutive prompt tokens at
+ * positions pos0 .. pos0+n_tokens-1 with causal attention (token i sees slots
+ * 0..pos0+i), filling cache slots pos0..pos0+n_tokens-1 and no others.
+ * Weights, h_in [n_tokens][h] and the KV cache are bf16; accumulation is fp32
+ * on the matrix cores; partial_out [n_tokens][h] is fp32.
+ * Errors as for decode; pos0 + n_tokens > max_seq is TPI_EINVAL;
+ * cfg.dtype != TPI_BF16 is TPI_EUNSUPPORTED.
+ */
+int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w,
+                            const tpi_kv_layer *host_kv, int32_t pos0, int32_t n_tokens,
+                            int phase, const void *h_in, float *partial_out, void *workspace,
+                            void *stream);
+
+/*
+ * Star all-reduce sum as the master performs it (Sec. 3.2, Prop. 2; the
+ * "+ H" shortcut of Eq. 1 and Eq. 2):
+ *   out[i] = (((p0[i] + p1[i]) + p2[i]) + ... + p_{n-1}[i]) + residual[i]
+ * in fp32, ranks in index order, shortcut last, no fused multiply-add and no
+ * reassociation: exactly one bit pattern is correct.
+ * host_partials: HOST array of n device pointers to [len] fp32.  residual may
+ * be NULL.  out may alias residual or any partial.
+ * Errors: TPI_EINVAL for n < 1, len < 0, null pointers; TPI_EUNSUPPORTED for
+ * n > TPI_MAX_REDUCE_RANKS.
+ */
+int tpi_star_reduce(const float *const *host_partials, int32_t n, int64_t len,
+                    const float *residual, float *out, void *stream);
+
+/*
+ * Sliding window of layer shards (Sec. 3.3; appendix "A simple-to-use memory
+ * scheduler").  All n_layers blobs live in pinned host memory; `window_layers`
+ * slots of layer_bytes each live in HBM.  Layer l always occupies slot
+ * l % window_layers.  The library owns one copy stream and two events per
+ * slot; copies run on the copy stream and overlap with whatever the compute
+ * stream is doing.
+ *
+ *   prefetch(l): enqueue the host-to-device copy of layer l into its slot, after
+ *                the slot's previous tenant was released.  Non-blocking.
+ *   acquire(l):  make compute_stream wait until layer l is resident; returns
+ *                the slot's device address ("wait" of wait_and_release).
+ *   release(l):  mark the slot reusable once compute_stream has finished what
+ *                was queued so far ("release" of wait_and_release).
+ *
+ * TPI_ESTATE: acquire of a layer that is not the slot's prefetched tenant,
+ * prefetch into a slot whose tenant is prefetched or acquired and not yet
+ * released, release of a layer that was not acquired.
+ * TPI_EINVAL: layer out of range, window_layers < 1, null pointers.
+ */
+typedef struct tpi_window tpi_window;
+
+int tpi_window_create(tpi_window **out, int32_t n_layers, int32_t window_layers,
+                      size_t layer_bytes, const void *const *host_layer_blobs,
+                      void *device_slots);
+int tpi_window_prefetch(tpi_window *w, int32_t layer);
+int tpi_window_acquire(tpi_window *w, int32_t layer, void *compute_stream,
+                       const void **dev_blob);
+int tpi_window_release(tpi_window *w, int32_t layer, void *compute_stream);
+/* Blocks until every queued copy has finished, then frees the object. */
+int tpi_window_destroy(tpi_window *w);
+/* Total time (ms) the copy stream spent in copies between the first prefetch
+ * and the last one completed so far, and the bytes they moved; synchronises
+ * the copy stream.  Either output may be NULL. */
+int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes);
+
+const char *tpi_last_error(void);
+
+/* ABI version of this header: bumped when a signature changes. */
+int tpi_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TPI_H */

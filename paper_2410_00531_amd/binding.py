@@ -1,0 +1,232 @@
+"""ctypes binding of libtpi.so: the same names as include/tpi.h, argument
+marshalling only.  Every step of the path runs in the library's HIP kernels;
+there is no fallback: a missing library raises.
+
+Tensors are torch CUDA tensors (PyTorch-ROCm is used for device memory and
+streams); the functions take their data pointers and the current stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtpi.so")
+
+TPI_OK, TPI_EINVAL, TPI_EUNSUPPORTED, TPI_ERUNTIME, TPI_ESTATE = 0, -1, -2, -3, -4
+TPI_F32, TPI_BF16 = 0, 1
+TPI_PHASE_ATTN, TPI_PHASE_FFN = 1, 2
+TPI_MAX_REDUCE_RANKS = 64
+TPI_MAX_BATCH_SHARDS = 16
+
+EXPORTED = (
+    "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode",
+    "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_window_create", "tpi_window_prefetch",
+    "tpi_window_acquire", "tpi_window_release", "tpi_window_destroy", "tpi_window_copy_stats",
+    "tpi_last_error", "tpi_abi_version",
+)
+
+
+class TpiError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libtpi error {code}: {msg}")
+        self.code = code
+
+
+class tpi_shard_cfg(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_local", C.c_int32), ("n_kv_local", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn_local", C.c_int32), ("max_seq", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32)]
+
+
+class tpi_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("attn_norm", "w_qkv", "w_o", "ffn_norm", "w_gate", "w_up", "w_down")]
+
+
+class tpi_kv_layer(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libtpi.so (built in-tree by ``build.build_lib``); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first "
+                               "(python -m paper_2410_00531_amd.build); there is no fallback path")
+        l = C.CDLL(LIB_PATH)
+        l.tpi_workspace_bytes.restype = C.c_size_t
+        l.tpi_workspace_bytes.argtypes = [C.POINTER(tpi_shard_cfg), C.c_int32]
+        l.tpi_last_error.restype = C.c_char_p
+        l.tpi_abi_version.restype = C.c_int
+        l.tpi_shard_layer_decode.restype = C.c_int
+        l.tpi_shard_layer_decode.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
+                                             C.POINTER(tpi_kv_layer), C.c_int32, C.c_int, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p]
+        l.tpi_shards_layer_decode.restype = C.c_int
+        l.tpi_shards_layer_decode.argtypes = [C.POINTER(tpi_shard_cfg), C.c_int32,
+                                              C.POINTER(tpi_layer_weights), C.POINTER(tpi_kv_layer),
+                                              C.c_int32, C.c_int, C.c_void_p, C.POINTER(C.c_void_p),
+                                              C.POINTER(C.c_void_p), C.c_void_p]
+        l.tpi_shard_layer_prefill.restype = C.c_int
+        l.tpi_shard_layer_prefill.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
+                                              C.POINTER(tpi_kv_layer), C.c_int32, C.c_int32, C.c_int,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.tpi_star_reduce.restype = C.c_int
+        l.tpi_star_reduce.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p,
+                                      C.c_void_p, C.c_void_p]
+        l.tpi_window_create.restype = C.c_int
+        l.tpi_window_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_size_t,
+                                        C.POINTER(C.c_void_p), C.c_void_p]
+        for name in ("tpi_window_prefetch",):
+            getattr(l, name).restype = C.c_int
+            getattr(l, name).argtypes = [C.c_void_p, C.c_int32]
+        l.tpi_window_acquire.restype = C.c_int
+        l.tpi_window_acquire.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]
+        l.tpi_window_release.restype = C.c_int
+        l.tpi_window_release.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        l.tpi_window_destroy.restype = C.c_int
+        l.tpi_window_destroy.argtypes = [C.c_void_p]
+        l.tpi_window_copy_stats.restype = C.c_int
+        l.tpi_window_copy_stats.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
+        _lib = l
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != TPI_OK:
+        raise TpiError(rc, lib().tpi_last_error().decode())
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def make_cfg(hidden, n_q_local, n_kv_local, head_dim, ffn_local, max_seq, rms_eps=1e-5,
+             rope_base=10000.0, dtype=TPI_F32) -> tpi_shard_cfg:
+    return tpi_shard_cfg(hidden, n_q_local, n_kv_local, head_dim, ffn_local, max_seq, rms_eps,
+                         rope_base, dtype)
+
+
+def make_weights(w) -> tpi_layer_weights:
+    """w: mapping with the seven tensors (torch tensors or raw device addresses)."""
+    return tpi_layer_weights(*[_ptr(w.get(n)) for n, _ in tpi_layer_weights._fields_])
+
+
+def make_kv(k, v) -> tpi_kv_layer:
+    return tpi_kv_layer(_ptr(k), _ptr(v))
+
+
+def tpi_abi_version() -> int:
+    return int(lib().tpi_abi_version())
+
+
+def tpi_last_error() -> str:
+    return lib().tpi_last_error().decode()
+
+
+def tpi_workspace_bytes(cfg: tpi_shard_cfg, n_tokens: int = 1) -> int:
+    return int(lib().tpi_workspace_bytes(C.byref(cfg), n_tokens))
+
+
+def tpi_shard_layer_decode(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_layer], pos: int,
+                           phase: int, h_in, partial_out, workspace, stream=None) -> None:
+    _check(lib().tpi_shard_layer_decode(C.byref(cfg), C.byref(weights),
+                                        C.byref(kv) if kv is not None else None, pos, phase,
+                                        _ptr(h_in), _ptr(partial_out), _ptr(workspace), _stream(stream)))
+
+
+def tpi_shards_layer_decode(cfg, weights: Sequence[tpi_layer_weights],
+                            kvs: Optional[Sequence[tpi_kv_layer]], pos: int, phase: int, h_in,
+                            partial_outs, workspaces, stream=None) -> None:
+    n = len(weights)
+    warr = weights if isinstance(weights, C.Array) else (tpi_layer_weights * n)(*weights)
+    if kvs is None:
+        karr = None
+    else:
+        karr = kvs if isinstance(kvs, C.Array) else (tpi_kv_layer * n)(*kvs)
+    parr = partial_outs if isinstance(partial_outs, C.Array) else (C.c_void_p * n)(*[_ptr(p) for p in partial_outs])
+    wsarr = workspaces if isinstance(workspaces, C.Array) else (C.c_void_p * n)(*[_ptr(p) for p in workspaces])
+    _check(lib().tpi_shards_layer_decode(C.byref(cfg), n, warr, karr, pos, phase, _ptr(h_in), parr,
+                                         wsarr, _stream(stream)))
+
+
+def tpi_shard_layer_prefill(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_layer], pos0: int,
+                            n_tokens: int, phase: int, h_in, partial_out, workspace, stream=None) -> None:
+    _check(lib().tpi_shard_layer_prefill(C.byref(cfg), C.byref(weights),
+                                         C.byref(kv) if kv is not None else None, pos0, n_tokens,
+                                         phase, _ptr(h_in), _ptr(partial_out), _ptr(workspace),
+                                         _stream(stream)))
+
+
+def tpi_star_reduce(partials, residual, out, length: Optional[int] = None, stream=None) -> None:
+    """partials: sequence of tensors / addresses (rank order) or a prepared
+    ``(c_void_p * n)`` array; length defaults to out.numel()."""
+    if isinstance(partials, C.Array):
+        arr, n = partials, len(partials)
+    else:
+        n = len(partials)
+        arr = (C.c_void_p * max(n, 1))(*[_ptr(p) for p in partials])
+    if length is None:
+        length = out.numel()
+    _check(lib().tpi_star_reduce(arr, n, length, _ptr(residual), _ptr(out), _stream(stream)))
+
+
+class Window:
+    """tpi_window_* as an object; ``slot(layer)`` mirrors the paper's
+    wait_and_release context manager."""
+
+    def __init__(self, host_blobs: Sequence[torch.Tensor], device_slots: torch.Tensor,
+                 window_layers: int, layer_bytes: int):
+        self._h = C.c_void_p()
+        self._keep = (list(host_blobs), device_slots)
+        n = len(host_blobs)
+        arr = (C.c_void_p * n)(*[_ptr(b) for b in host_blobs])
+        _check(lib().tpi_window_create(C.byref(self._h), n, window_layers, layer_bytes, arr,
+                                       _ptr(device_slots)))
+
+    def prefetch(self, layer: int) -> None:
+        _check(lib().tpi_window_prefetch(self._h, layer))
+
+    def acquire(self, layer: int, stream=None) -> int:
+        out = C.c_void_p()
+        _check(lib().tpi_window_acquire(self._h, layer, _stream(stream), C.byref(out)))
+        return out.value
+
+    def release(self, layer: int, stream=None) -> None:
+        _check(lib().tpi_window_release(self._h, layer, _stream(stream)))
+
+    def copy_stats(self):
+        ms, b = C.c_double(), C.c_uint64()
+        _check(lib().tpi_window_copy_stats(self._h, C.byref(ms), C.byref(b)))
+        return ms.value, b.value
+
+    def destroy(self) -> None:
+        if self._h:
+            h, self._h = self._h, C.c_void_p()
+            _check(lib().tpi_window_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,20 @@
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tpi {
+
+constexpr int kMaxReduceRanks = 64;   // == TPI_MAX_REDUCE_RANKS
+
+struct ReduceArgs {
+    const float *p[kMaxReduceRanks];
+    const float *residual;   // nullable
+    float *out;
+    int64_t len;
+    int n;
+    int vec_ok;              // all pointers 16-byte aligned
+};
+
+hipError_t launch_star_reduce(const ReduceArgs &a, hipStream_t st);
+
+}  // namespace tpi

@@ -1,0 +1,114 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before queuing anything (no
+compute call is made here; pointers are fake and never dereferenced)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2410_00531_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000          # a non-null, 16-byte aligned address that is never touched
+
+
+def _header_functions():
+    txt = open(os.path.join(ROOT, "include", "tpi.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(tpi_[a-z_0-9]+)\s*\(", txt)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _header_functions()
+    assert set(names) == set(B.EXPORTED), (names, B.EXPORTED)
+    lib = B.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert B.tpi_abi_version() == 1
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(B.tpi_shard_cfg) == 36
+    assert C.sizeof(B.tpi_layer_weights) == 56
+    assert C.sizeof(B.tpi_kv_layer) == 16
+
+
+def _w():
+    return B.tpi_layer_weights(*([FAKE] * 7))
+
+
+def _code(fn, *a, **k):
+    with pytest.raises(B.TpiError) as ei:
+        fn(*a, **k)
+    return ei.value.code
+
+
+def test_workspace_bytes():
+    cfg = B.make_cfg(8192, 8, 1, 128, 3584, 1100)
+    n = B.tpi_workspace_bytes(cfg, 1)
+    # q + split maxima and sums + split outputs + activation, in floats
+    assert n == 4 * (1024 + 2 * 8 * 32 + 8 * 32 * 128 + 3584)
+    assert B.tpi_workspace_bytes(B.make_cfg(8192, 8, 3, 128, 3584, 1100), 1) == 0
+    assert B.tpi_workspace_bytes(cfg, 0) == 0
+
+
+def test_decode_argument_errors():
+    good = B.make_cfg(256, 2, 2, 64, 344, 24)
+    kv = B.tpi_kv_layer(FAKE, FAKE)
+    call = lambda cfg, pos=3, phase=B.TPI_PHASE_ATTN, w=None, kvv=kv, h=FAKE, out=FAKE, ws=FAKE: \
+        B.tpi_shard_layer_decode(cfg, w or _w(), kvv, pos, phase, h, out, ws, stream=0)
+    assert _code(call, good, pos=-1) == B.TPI_EINVAL
+    assert _code(call, good, pos=24) == B.TPI_EINVAL
+    assert _code(call, good, phase=7) == B.TPI_EINVAL
+    assert _code(call, good, h=None) == B.TPI_EINVAL
+    assert _code(call, good, out=None) == B.TPI_EINVAL
+    assert _code(call, good, ws=None) == B.TPI_EINVAL
+    assert _code(call, good, kvv=None) == B.TPI_EINVAL
+    assert _code(call, good, kvv=B.tpi_kv_layer(FAKE, None)) == B.TPI_EINVAL
+    wbad = _w(); wbad.w_o = None
+    assert _code(call, good, w=wbad) == B.TPI_EINVAL
+    assert _code(call, B.make_cfg(256, 3, 2, 64, 344, 24)) == B.TPI_EINVAL       # heads not a multiple
+    assert _code(call, B.make_cfg(256, 2, 2, 63, 344, 24)) == B.TPI_EINVAL       # odd head size
+    assert _code(call, B.make_cfg(0, 2, 2, 64, 344, 24)) == B.TPI_EINVAL
+    assert _code(call, B.make_cfg(256, 2, 2, 64, 344, 0)) == B.TPI_EINVAL
+    assert _code(call, B.make_cfg(256, 2, 2, 64, 344, 24, dtype=5)) == B.TPI_EINVAL
+    assert _code(call, B.make_cfg(256, 2, 2, 66, 344, 24)) == B.TPI_EUNSUPPORTED  # not a multiple of 4
+    assert _code(call, B.make_cfg(256, 2, 2, 512, 344, 24)) == B.TPI_EUNSUPPORTED
+    assert _code(call, B.make_cfg(256, 2, 2, 64, 344, 24, dtype=B.TPI_BF16)) == B.TPI_EUNSUPPORTED
+    assert _code(call, good, h=FAKE + 4) == B.TPI_EUNSUPPORTED                   # misaligned
+    assert "aligned" in B.tpi_last_error()
+    # batched variant: shard count limits
+    n = B.TPI_MAX_BATCH_SHARDS + 1
+    assert _code(B.tpi_shards_layer_decode, good, [_w()] * n, [kv] * n, 3, B.TPI_PHASE_ATTN, FAKE,
+                 [FAKE] * n, [FAKE] * n, stream=0) == B.TPI_EINVAL
+
+
+def test_star_reduce_and_prefill_argument_errors():
+    assert _code(B.tpi_star_reduce, [], None, FAKE, length=4, stream=0) == B.TPI_EINVAL
+    assert _code(B.tpi_star_reduce, [FAKE], None, FAKE, length=-1, stream=0) == B.TPI_EINVAL
+    assert _code(B.tpi_star_reduce, [FAKE, None], None, FAKE, length=4, stream=0) == B.TPI_EINVAL
+    assert _code(B.tpi_star_reduce, [FAKE], None, None, length=4, stream=0) == B.TPI_EINVAL
+    assert _code(B.tpi_star_reduce, [FAKE] * 65, None, FAKE, length=4, stream=0) == B.TPI_EUNSUPPORTED
+    cfg = B.make_cfg(256, 2, 2, 64, 344, 24, dtype=B.TPI_BF16)
+    kv = B.tpi_kv_layer(FAKE, FAKE)
+    pre = lambda c, pos0, n: B.tpi_shard_layer_prefill(c, _w(), kv, pos0, n, B.TPI_PHASE_ATTN, FAKE, FAKE,
+                                                       FAKE, stream=0)
+    assert _code(pre, cfg, 20, 5) == B.TPI_EINVAL
+    assert _code(pre, cfg, -1, 5) == B.TPI_EINVAL
+    assert _code(pre, cfg, 0, 0) == B.TPI_EINVAL
+    assert _code(pre, B.make_cfg(256, 2, 2, 64, 344, 24), 0, 4) == B.TPI_EUNSUPPORTED   # fp32 prefill
+
+
+def test_window_argument_errors_without_a_device():
+    h = C.c_void_p()
+    lib = B.lib()
+    arr = (C.c_void_p * 2)(FAKE, FAKE)
+    assert lib.tpi_window_create(C.byref(h), 0, 1, 16, arr, FAKE) == B.TPI_EINVAL
+    assert lib.tpi_window_create(C.byref(h), 2, 0, 16, arr, FAKE) == B.TPI_EINVAL
+    assert lib.tpi_window_create(C.byref(h), 2, 1, 0, arr, FAKE) == B.TPI_EINVAL
+    assert lib.tpi_window_create(C.byref(h), 2, 1, 16, None, FAKE) == B.TPI_EINVAL
+    arr2 = (C.c_void_p * 2)(FAKE, None)
+    assert lib.tpi_window_create(C.byref(h), 2, 1, 16, arr2, FAKE) == B.TPI_EINVAL
+    assert lib.tpi_window_prefetch(None, 0) == B.TPI_EINVAL
+    assert lib.tpi_window_destroy(None) == B.TPI_EINVAL
