@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""Decode benchmark of the TPI-LLM shard path on one MI355X.
+
+One step = one token through the whole layer stack: for every layer, the
+attention phase of all N emulated shards, the fixed-order star reduce with the
+shortcut, the FFN phase of all shards, and the second star reduce.  Default
+workload: Llama-2-70B-shaped stack (80 layers, hidden 8192, 64 query / 8 KV
+heads of 128, FFN 28672) cut 8 ways, every shard's fp32 weights resident in
+HBM (273.85 GB), batch 1, KV length 1024, synthetic seeded data.
+
+Prints ONE JSON line.  `value` is ms per token for the whole emulated job (all
+8 shards on this one GPU); `one_shard` gives the same token for a single
+device's shard (what one TPI-LLM device executes), with the 8-way reduce still
+running on 7 pre-filled peer partials.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama2-70b-shaped-tp8",
+                    choices=["llama2-70b-shaped-tp8", "llama3.1-8b-shaped-tp4", "tiny"])
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
+    ap.add_argument("--kv-len", type=int, default=0, help="tokens already cached (default 1024 / 512 / 16)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+def blob_layout(m):
+    """Offsets (floats) of the seven tensors inside one layer-shard blob."""
+    from paper_2410_00531_amd import synth
+    shapes = synth.shard_tensor_shapes(m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local)
+    off, out = 0, {}
+    for name in synth.TENSOR_ORDER:
+        n = 1
+        for s in shapes[name]:
+            n *= s
+        out[name] = (off, shapes[name], n)
+        off += n
+    return out, off
+
+
+def stage_bytes(m, n_shards, pos):
+    """Algorithmic bytes one launch of each stage moves (fp32): the weights it
+    must read once, its input and output vectors, and the KV rows."""
+    h, d, sl = m.hidden, m.head_dim, m.ffn_local
+    dq, dkv = m.nq_local * d, m.nkv_local * d
+    f = 4
+    per = {
+        "qkv": ((dq + 2 * dkv) * h + 2 * h + dq + 2 * dkv) * f,
+        "attn": (2 * dkv * (pos + 1) + 2 * dq) * f,
+        "oproj": (h * dq + dq + h) * f,
+        "gate_up": (2 * sl * h + 2 * h + sl) * f,
+        "down": (h * sl + sl + h) * f,
+    }
+    return {k: v * n_shards for k, v in per.items()}
+
+
+def token_bytes(m, n_shards, n_reduce, n_layers, pos):
+    sb = stage_bytes(m, n_shards, pos)
+    reduce_b = (n_reduce + 2) * m.hidden * 4          # N partials + shortcut read, one write
+    return n_layers * (sum(sb.values()) + 2 * reduce_b)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the N shards of the tensor-parallel layer are emulated "
+              "on it and no multi-GPU figure exists. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2410_00531_amd import binding as B
+    from paper_2410_00531_amd import configs, synth
+
+    m = configs.BY_NAME[args.workload]
+    L = args.layers or m.n_layers
+    N = m.n_shards
+    kv_len = args.kv_len or {"llama2-70b-shaped-tp8": 1024, "llama3.1-8b-shaped-tp4": 512, "tiny": 16}[args.workload]
+    K, W = args.steps, args.warmup
+    n_tokens_total = 4 * (K + W) + 8
+    max_seq = kv_len + n_tokens_total
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B.lib()
+    cfg = B.make_cfg(m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local, max_seq, m.rms_eps, m.rope_base)
+    layout, blob_floats = blob_layout(m)
+    assert blob_floats == m.layer_shard_params()
+
+    # ---- synthetic stack, drawn on the device (seeded) ------------------------------------------
+    gen = torch.Generator(device=dev); gen.manual_seed(args.seed)
+    t0 = time.time()
+    blobs = []                                            # [layer] tensor [N][blob_floats]
+    for l in range(L):
+        b = torch.empty((N, blob_floats), dtype=torch.float32, device=dev)
+        b.normal_(0.0, synth.WEIGHT_STD, generator=gen)
+        for name in ("attn_norm", "ffn_norm"):
+            off, _, n = layout[name]
+            b[:, off:off + n] += 1.0
+        blobs.append(b)
+    kc = torch.zeros((L, N, 2, m.nkv_local, max_seq, m.head_dim), dtype=torch.float32, device=dev)
+    kc[:, :, :, :, :kv_len].normal_(0.0, 1.0, generator=gen)
+    h0 = torch.randn(m.hidden, generator=gen, device=dev)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    # ---- pre-marshalled argument blocks ---------------------------------------------------------
+    esz = 4
+    W_all, KV_all, W_one, KV_one = [], [], [], []
+    for l in range(L):
+        wl = (B.tpi_layer_weights * N)()
+        kl = (B.tpi_kv_layer * N)()
+        for r in range(N):
+            base = blobs[l][r].data_ptr()
+            for name in synth.TENSOR_ORDER:
+                setattr(wl[r], name, base + layout[name][0] * esz)
+            kl[r].k = kc[l, r, 0].data_ptr(); kl[r].v = kc[l, r, 1].data_ptr()
+        W_all.append(wl); KV_all.append(kl)
+        W_one.append((B.tpi_layer_weights * 1)(wl[0])); KV_one.append((B.tpi_kv_layer * 1)(kl[0]))
+    ws_bytes = B.tpi_workspace_bytes(cfg, 1)
+    ws = torch.empty((N, ws_bytes // 4), dtype=torch.float32, device=dev)
+    partials = torch.zeros((N, m.hidden), dtype=torch.float32, device=dev)
+    P_all = (C.c_void_p * N)(*[partials[r].data_ptr() for r in range(N)])
+    WS_all = (C.c_void_p * N)(*[ws[r].data_ptr() for r in range(N)])
+    P_one = (C.c_void_p * 1)(partials[0].data_ptr())
+    WS_one = (C.c_void_p * 1)(ws[0].data_ptr())
+    h_a = torch.empty_like(h0); h_b = torch.empty_like(h0); h_attn = torch.empty_like(h0)
+
+    lib = B.lib()
+    stream = torch.cuda.current_stream().cuda_stream
+    cfg_p = C.byref(cfg)
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(B.tpi_last_error())
+
+    def token(pos, all_shards=True):
+        """One token through the stack; returns the output hidden state tensor."""
+        Wl, KVl, Pl, WSl, n = (W_all, KV_all, P_all, WS_all, N) if all_shards else (W_one, KV_one, P_one, WS_one, 1)
+        src, dst = h0, h_a
+        for l in range(L):
+            check(lib.tpi_shards_layer_decode(cfg_p, n, Wl[l], KVl[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
+                                              Pl, WSl, stream))
+            check(lib.tpi_star_reduce(P_all, N, m.hidden, src.data_ptr(), h_attn.data_ptr(), stream))
+            check(lib.tpi_shards_layer_decode(cfg_p, n, Wl[l], None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
+                                              Pl, WSl, stream))
+            check(lib.tpi_star_reduce(P_all, N, m.hidden, h_attn.data_ptr(), dst.data_ptr(), stream))
+            src, dst = dst, (h_b if dst is h_a else h_a)
+        return src
+
+    def timed(n_steps, pos0, all_shards):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_steps)]
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(n_steps):
+            ev[i][0].record()
+            token(pos0 + i, all_shards)
+            ev[i][1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t
+        per = sorted(a.elapsed_time(b) for a, b in ev)
+        return wall * 1e3 / n_steps, per[len(per) // 2], per[0]
+
+    pos = kv_len
+    for i in range(W):
+        token(pos + i);
+    pos += W
+    ms_all, med_all, min_all = timed(K, pos, True); pos += K
+    out = token(pos - 1, True)
+    finite = bool(torch.isfinite(out).all().item())
+
+    # roofline leg: the same K steps with HIP events around every launch of the dominant kernel
+    B.tpi_prof_enable(B.TPI_STAGE_GATE_UP, K * L)
+    timed(K, pos, True); pos += K
+    gu_ms, gu_n = B.tpi_prof_read()
+    B.tpi_prof_enable(B.TPI_STAGE_NONE, 0)
+
+    # one device's shard (peer partials stay as the last full step left them)
+    for i in range(W):
+        token(pos + i, False)
+    pos += W
+    ms_one, med_one, min_one = timed(K, pos, False); pos += K
+    B.tpi_prof_enable(B.TPI_STAGE_GATE_UP, K * L)
+    timed(K, pos, False); pos += K
+    gu1_ms, gu1_n = B.tpi_prof_read()
+    B.tpi_prof_enable(B.TPI_STAGE_NONE, 0)
+    assert pos <= max_seq
+
+    mid_pos = kv_len + W + K // 2
+    bytes_all = token_bytes(m, N, N, L, mid_pos)
+    bytes_one = token_bytes(m, 1, N, L, mid_pos)
+    gbps_all = bytes_all / (ms_all * 1e-3) / 1e9
+    gbps_one = bytes_one / (ms_one * 1e-3) / 1e9
+    gu_bytes = stage_bytes(m, N, mid_pos)["gate_up"]
+    gu_avg_ms = gu_ms / max(gu_n, 1)
+    gu_gbps = gu_bytes / (gu_avg_ms * 1e-3) / 1e9 if gu_n else 0.0
+    gu1_bytes = stage_bytes(m, 1, mid_pos)["gate_up"]
+    gu1_avg_ms = gu1_ms / max(gu1_n, 1)
+
+    result = {
+        "metric": "decode_ms_per_token",
+        "value": round(ms_all, 4),
+        "unit": "ms/token",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_all, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{m.name}-resident-decode", "layers": L, "shards_emulated": N,
+                   "hidden": m.hidden, "q_heads_per_shard": m.nq_local, "kv_heads_per_shard": m.nkv_local,
+                   "head_dim": m.head_dim, "ffn_per_shard": m.ffn_local, "kv_len": kv_len, "batch": 1,
+                   "weights_gb": round(L * N * blob_floats * 4 / 1e9, 2)},
+        "tokens_per_s": round(1e3 / ms_all, 3),
+        "ms_per_token_median_events": round(med_all, 4),
+        "algorithmic_gb_per_token": round(bytes_all / 1e9, 3),
+        "hbm_gbps": round(gbps_all, 1),
+        "hbm_frac_of_peak": round(gbps_all / HBM_PEAK_GBPS, 4),
+        "one_shard": {"ms_per_token": round(ms_one, 4), "ms_per_token_median_events": round(med_one, 4),
+                      "tokens_per_s": round(1e3 / ms_one, 2),
+                      "algorithmic_gb_per_token": round(bytes_one / 1e9, 3), "hbm_gbps": round(gbps_one, 1),
+                      "hbm_frac_of_peak": round(gbps_one / HBM_PEAK_GBPS, 4),
+                      "gate_up_kernel_avg_us": round(gu1_avg_ms * 1e3, 2),
+                      "gate_up_kernel_gbps": round(gu1_bytes / (gu1_avg_ms * 1e-3) / 1e9, 1) if gu1_n else None},
+        "roofline": {"kernel": "k_gate_up (RMSNorm + gate/up GEMV + SiLU gate, 8 shards per launch)",
+                     "bound": "hbm", "achieved": round(gu_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": gu_bytes, "avg_launch_us": round(gu_avg_ms * 1e3, 2), "launches": gu_n},
+        "output_finite": finite,
+        "setup_s": round(setup_s, 1),
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample ------------------------------
+    if not args.no_cpu_baseline:
+        from oracle import tpi_oracle as O
+        oc = O.ShardCfg(m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local, max_seq, m.rms_eps, m.rope_base)
+        w = {name: blobs[0][0][layout[name][0]:layout[name][0] + layout[name][2]].reshape(layout[name][1]).cpu().numpy()
+             for name in synth.TENSOR_ORDER}
+        Kc = kc[0, 0, 0].cpu().numpy().copy(); Vc = kc[0, 0, 1].cpu().numpy().copy()
+        x = h0.cpu().numpy()
+        reps, spent = 0, 0.0
+        while spent < args.cpu_seconds and reps < 100000:
+            t = time.perf_counter()
+            pa = O.attn_block(oc, w["attn_norm"], w["w_qkv"], w["w_o"], Kc, Vc, kv_len, x)
+            O.ffn_block(oc, w["ffn_norm"], w["w_gate"], w["w_up"], w["w_down"], pa.astype(np.float32))
+            O.reduce_seq_f32([pa.astype(np.float32)] * N, x)
+            spent += time.perf_counter() - t
+            reps += 1
+        per_layer_shard_ms = spent / reps * 1e3
+        result["cpu_baseline"] = {
+            "value": round(per_layer_shard_ms * L * N, 1), "unit": "ms/token", "cores": O.num_threads(),
+            "kind": "oracle",
+            "sample": f"{reps} x one layer of one shard (attention block + FFN block + one {N}-way reduce) at the "
+                      f"workload's shape, {per_layer_shard_ms:.2f} ms each, scaled x{L} layers x{N} shards",
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -193,6 +193,21 @@ int tpi_window_destroy(tpi_window *w);
  * the copy stream.  Either output may be NULL. */
 int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes);
 
+/*
+ * Measurement aid (not part of the method): time every launch of one stage
+ * with HIP events recorded on the stream the kernel is launched on.
+ *   stage: 0 off, 1 QKV+rotary, 2 attention, 3 output projection,
+ *          4 gate/up, 5 down projection, 6 star reduce.
+ * tpi_prof_enable allocates `capacity` event pairs (launches beyond that are
+ * not timed) and clears earlier records; tpi_prof_read waits for the recorded
+ * launches, returns the sum of their durations and their count, and clears
+ * the records.  Not thread-safe; leave it off in production loops.
+ */
+enum { TPI_STAGE_NONE = 0, TPI_STAGE_QKV = 1, TPI_STAGE_ATTN = 2, TPI_STAGE_OPROJ = 3,
+       TPI_STAGE_GATE_UP = 4, TPI_STAGE_DOWN = 5, TPI_STAGE_REDUCE = 6 };
+int tpi_prof_enable(int stage, int32_t capacity);
+int tpi_prof_read(double *total_ms, int32_t *launches);
+
 const char *tpi_last_error(void);
 
 /* ABI version of this header: bumped when a signature changes. */

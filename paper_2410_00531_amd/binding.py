@@ -26,8 +26,10 @@ EXPORTED = (
     "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode",
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_window_create", "tpi_window_prefetch",
     "tpi_window_acquire", "tpi_window_release", "tpi_window_destroy", "tpi_window_copy_stats",
-    "tpi_last_error", "tpi_abi_version",
+    "tpi_last_error", "tpi_abi_version", "tpi_prof_enable", "tpi_prof_read",
 )
+TPI_STAGE_NONE, TPI_STAGE_QKV, TPI_STAGE_ATTN, TPI_STAGE_OPROJ = 0, 1, 2, 3
+TPI_STAGE_GATE_UP, TPI_STAGE_DOWN, TPI_STAGE_REDUCE = 4, 5, 6
 
 
 class TpiError(RuntimeError):
@@ -96,6 +98,10 @@ def lib() -> C.CDLL:
         l.tpi_window_destroy.argtypes = [C.c_void_p]
         l.tpi_window_copy_stats.restype = C.c_int
         l.tpi_window_copy_stats.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
+        l.tpi_prof_enable.restype = C.c_int
+        l.tpi_prof_enable.argtypes = [C.c_int, C.c_int32]
+        l.tpi_prof_read.restype = C.c_int
+        l.tpi_prof_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         _lib = l
     return _lib
 
@@ -189,6 +195,17 @@ def tpi_star_reduce(partials, residual, out, length: Optional[int] = None, strea
     if length is None:
         length = out.numel()
     _check(lib().tpi_star_reduce(arr, n, length, _ptr(residual), _ptr(out), _stream(stream)))
+
+
+def tpi_prof_enable(stage: int, capacity: int = 0) -> None:
+    _check(lib().tpi_prof_enable(stage, capacity))
+
+
+def tpi_prof_read():
+    """(sum of the timed launches' durations in ms, number of launches)."""
+    ms, n = C.c_double(), C.c_int32()
+    _check(lib().tpi_prof_read(C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 class Window:

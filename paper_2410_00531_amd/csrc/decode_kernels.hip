@@ -13,6 +13,7 @@
 // touched: weights never depend on activations, so their latency overlaps the
 // prologue (norm, merge) of the stage.
 #include "decode_args.hpp"
+#include "prof.hpp"
 #include "tpi_device.hpp"
 
 namespace tpi {
@@ -401,12 +402,14 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
     {
         constexpr int PAIRS = 2, U = 4;
         size_t lds = sizeof(float) * ((size_t)a.h + 2 * PAIRS * kWavesPerBlock + kWavesPerBlock);
+        ProfScope ps(kStageQkv, st);
         hipLaunchKernelGGL((k_qkv_rope<PAIRS, U>), dim3(cdiv(npairs, PAIRS), n_shards), dim3(kBlock), lds, st, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     {
         const int G = a.nq / a.nkv;
+        ProfScope ps(kStageAttn, st);
         hipError_t e;
         if (G == 1) e = launch_attn_gt<1>(a, n_shards, st);
         else if (G == 2) e = launch_attn_gt<2>(a, n_shards, st);
@@ -418,6 +421,7 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         constexpr int ROWS = 8, U = 2;
         const int dq = a.nq * a.d;
         size_t lds = sizeof(float) * ((size_t)dq + ROWS * kWavesPerBlock);
+        ProfScope ps(kStageOproj, st);
         hipLaunchKernelGGL((k_oproj<ROWS, U>), dim3(cdiv(a.h, ROWS), n_shards), dim3(kBlock), lds, st, a);
         return hipGetLastError();
     }
@@ -428,6 +432,7 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
     {
         constexpr int COLS = 2, U = 4;
         size_t lds = sizeof(float) * ((size_t)a.h + 2 * COLS * kWavesPerBlock + kWavesPerBlock);
+        ProfScope ps(kStageGateUp, st);
         hipLaunchKernelGGL((k_gate_up<COLS, U>), dim3(cdiv(a.sl, COLS), n_shards), dim3(kBlock), lds, st, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -435,6 +440,7 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
     {
         constexpr int ROWS = 8, U = 2;
         size_t lds = sizeof(float) * ((size_t)a.sl + ROWS * kWavesPerBlock);
+        ProfScope ps(kStageDown, st);
         hipLaunchKernelGGL((k_down<ROWS, U>), dim3(cdiv(a.h, ROWS), n_shards), dim3(kBlock), lds, st, a);
         return hipGetLastError();
     }

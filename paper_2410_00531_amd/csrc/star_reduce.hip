@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "prof.hpp"
 #include "star_reduce.hpp"
 
 namespace tpi {
@@ -42,6 +43,7 @@ hipError_t launch_star_reduce(const ReduceArgs &a, hipStream_t st)
     int64_t blocks = (work + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
+    ProfScope ps(kStageReduce, st);
     hipLaunchKernelGGL(k_star_reduce, dim3((unsigned)blocks), dim3(256), 0, st, a);
     return hipGetLastError();
 }
