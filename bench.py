@@ -38,6 +38,10 @@ def parse():
                     choices=["llama2-70b-shaped-tp8", "llama3.1-8b-shaped-tp4", "tiny"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--kv-len", type=int, default=0, help="tokens already cached (default 1024 / 512 / 16)")
+    ap.add_argument("--mode", default="both", choices=["both", "all", "one"],
+                    help="all: only the 8-shard emulated job; one: only one device's shard; both (default)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference row for rocprofv3 --pmc byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
     ap.add_argument("--seed", type=int, default=0)
@@ -153,6 +157,8 @@ def main():
         if rc != 0:
             raise RuntimeError(B.tpi_last_error())
 
+    last_out = [h0]
+
     def token(pos, all_shards=True):
         """One token through the stack; returns the output hidden state tensor."""
         Wl, KVl, Pl, WSl, n = (W_all, KV_all, P_all, WS_all, N) if all_shards else (W_one, KV_one, P_one, WS_one, 1)
@@ -165,6 +171,7 @@ def main():
                                               Pl, WSl, stream))
             check(lib.tpi_star_reduce(P_all, N, m.hidden, h_attn.data_ptr(), dst.data_ptr(), stream))
             src, dst = dst, (h_b if dst is h_a else h_a)
+        last_out[0] = src
         return src
 
     def timed(n_steps, pos0, all_shards):
@@ -180,37 +187,52 @@ def main():
         per = sorted(a.elapsed_time(b) for a, b in ev)
         return wall * 1e3 / n_steps, per[len(per) // 2], per[0]
 
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    def leg(all_shards):
+        """W warm-up tokens, K timed tokens, then the same K tokens again with HIP events
+        around every launch of the dominant kernel (gate/up)."""
+        nonlocal pos
+        for i in range(W):
+            token(pos + i, all_shards)
+        pos += W
+        ms, med, mn = timed(K, pos, all_shards); pos += K
+        B.tpi_prof_enable(B.TPI_STAGE_GATE_UP, K * L)
+        timed(K, pos, all_shards); pos += K
+        k_ms, k_n = B.tpi_prof_read()
+        B.tpi_prof_enable(B.TPI_STAGE_NONE, 0)
+        return ms, med, k_ms, k_n
+
     pos = kv_len
-    for i in range(W):
-        token(pos + i);
-    pos += W
-    ms_all, med_all, min_all = timed(K, pos, True); pos += K
-    out = token(pos - 1, True)
-    finite = bool(torch.isfinite(out).all().item())
-
-    # roofline leg: the same K steps with HIP events around every launch of the dominant kernel
-    B.tpi_prof_enable(B.TPI_STAGE_GATE_UP, K * L)
-    timed(K, pos, True); pos += K
-    gu_ms, gu_n = B.tpi_prof_read()
-    B.tpi_prof_enable(B.TPI_STAGE_NONE, 0)
-
-    # one device's shard (peer partials stay as the last full step left them)
-    for i in range(W):
-        token(pos + i, False)
-    pos += W
-    ms_one, med_one, min_one = timed(K, pos, False); pos += K
-    B.tpi_prof_enable(B.TPI_STAGE_GATE_UP, K * L)
-    timed(K, pos, False); pos += K
-    gu1_ms, gu1_n = B.tpi_prof_read()
-    B.tpi_prof_enable(B.TPI_STAGE_NONE, 0)
+    ms_all = med_all = gu_ms = ms_one = med_one = gu1_ms = float("nan")
+    gu_n = gu1_n = 0
+    if args.mode in ("both", "all"):
+        ms_all, med_all, gu_ms, gu_n = leg(True)
+    else:
+        token(pos, True); pos += 1                 # fills the peer partials once
+    if args.mode in ("both", "one"):
+        # one device's shard (peer partials stay as the last full step left them)
+        ms_one, med_one, gu1_ms, gu1_n = leg(False)
+    if args.mode == "one":
+        ms_all, med_all, gu_ms, gu_n = ms_one, med_one, gu1_ms, gu1_n
     assert pos <= max_seq
+    torch.cuda.synchronize()
+    finite = bool(torch.isfinite(last_out[0]).all().item())
 
     mid_pos = kv_len + W + K // 2
     bytes_all = token_bytes(m, N, N, L, mid_pos)
     bytes_one = token_bytes(m, 1, N, L, mid_pos)
     gbps_all = bytes_all / (ms_all * 1e-3) / 1e9
-    gbps_one = bytes_one / (ms_one * 1e-3) / 1e9
-    gu_bytes = stage_bytes(m, N, mid_pos)["gate_up"]
+    gbps_one = bytes_one / (ms_one * 1e-3) / 1e9 if args.mode != "all" else float("nan")
+    n_launch_shards = 1 if args.mode == "one" else N
+    if args.mode == "one":
+        bytes_all, gbps_all = bytes_one, gbps_one
+    gu_bytes = stage_bytes(m, n_launch_shards, mid_pos)["gate_up"]
     gu_avg_ms = gu_ms / max(gu_n, 1)
     gu_gbps = gu_bytes / (gu_avg_ms * 1e-3) / 1e9 if gu_n else 0.0
     gu1_bytes = stage_bytes(m, 1, mid_pos)["gate_up"]
@@ -227,7 +249,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{m.name}-resident-decode", "layers": L, "shards_emulated": N,
+        "config": {"workload": f"{m.name}-resident-decode" + ("-one-shard" if args.mode == "one" else ""),
+                   "layers": L, "shards_emulated": n_launch_shards, "shards_reduced": N,
                    "hidden": m.hidden, "q_heads_per_shard": m.nq_local, "kv_heads_per_shard": m.nkv_local,
                    "head_dim": m.head_dim, "ffn_per_shard": m.ffn_local, "kv_len": kv_len, "batch": 1,
                    "weights_gb": round(L * N * blob_floats * 4 / 1e9, 2)},
@@ -236,13 +259,13 @@ def main():
         "algorithmic_gb_per_token": round(bytes_all / 1e9, 3),
         "hbm_gbps": round(gbps_all, 1),
         "hbm_frac_of_peak": round(gbps_all / HBM_PEAK_GBPS, 4),
-        "one_shard": {"ms_per_token": round(ms_one, 4), "ms_per_token_median_events": round(med_one, 4),
+        "one_shard": None if args.mode == "all" else {"ms_per_token": round(ms_one, 4), "ms_per_token_median_events": round(med_one, 4),
                       "tokens_per_s": round(1e3 / ms_one, 2),
                       "algorithmic_gb_per_token": round(bytes_one / 1e9, 3), "hbm_gbps": round(gbps_one, 1),
                       "hbm_frac_of_peak": round(gbps_one / HBM_PEAK_GBPS, 4),
                       "gate_up_kernel_avg_us": round(gu1_avg_ms * 1e3, 2),
                       "gate_up_kernel_gbps": round(gu1_bytes / (gu1_avg_ms * 1e-3) / 1e9, 1) if gu1_n else None},
-        "roofline": {"kernel": "k_gate_up (RMSNorm + gate/up GEMV + SiLU gate, 8 shards per launch)",
+        "roofline": {"kernel": f"k_gate_up (RMSNorm + gate/up GEMV + SiLU gate, {n_launch_shards} shard(s) per launch)",
                      "bound": "hbm", "achieved": round(gu_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                      "bytes_per_launch": gu_bytes, "avg_launch_us": round(gu_avg_ms * 1e3, 2), "launches": gu_n},
