@@ -160,21 +160,24 @@ int tpi_star_reduce(const float *const *host_partials, int32_t n, int64_t len,
 /*
  * Sliding window of layer shards (Sec. 3.3; appendix "A simple-to-use memory
  * scheduler").  All n_layers blobs live in pinned host memory; `window_layers`
- * slots of layer_bytes each live in HBM.  Layer l always occupies slot
- * l % window_layers.  The library owns one copy stream and two events per
- * slot; copies run on the copy stream and overlap with whatever the compute
- * stream is doing.
+ * slots of layer_bytes each live in HBM and are used in ring order: the k-th
+ * prefetch lands in slot k % window_layers, so the window slides over the
+ * layers of one token and on into the next token's first layers.  The library
+ * owns one copy stream and two events per slot; copies run on the copy stream
+ * and overlap with whatever the compute stream is doing.
  *
- *   prefetch(l): enqueue the host-to-device copy of layer l into its slot, after
- *                the slot's previous tenant was released.  Non-blocking.
- *   acquire(l):  make compute_stream wait until layer l is resident; returns
- *                the slot's device address ("wait" of wait_and_release).
- *   release(l):  mark the slot reusable once compute_stream has finished what
+ *   prefetch(l): enqueue the host-to-device copy of layer l into the next ring
+ *                slot, after that slot's previous tenant was released.
+ *                Non-blocking.
+ *   acquire(l):  make compute_stream wait until the oldest prefetched copy of
+ *                layer l is resident; returns its device address ("wait" of
+ *                wait_and_release).
+ *   release(l):  mark that slot reusable once compute_stream has finished what
  *                was queued so far ("release" of wait_and_release).
  *
- * TPI_ESTATE: acquire of a layer that is not the slot's prefetched tenant,
- * prefetch into a slot whose tenant is prefetched or acquired and not yet
- * released, release of a layer that was not acquired.
+ * TPI_ESTATE: prefetch while the next ring slot's tenant is prefetched or
+ * acquired and not yet released (the window is full), acquire of a layer with
+ * no prefetched copy in the window, release of a layer that was not acquired.
  * TPI_EINVAL: layer out of range, window_layers < 1, null pointers.
  */
 typedef struct tpi_window tpi_window;

@@ -31,6 +31,17 @@ struct tpi_window {
     hipEvent_t first_begin = nullptr, last_done = nullptr;   // timing span of the copies
     bool any_copy = false;
     uint64_t bytes_copied = 0;
+    uint64_t n_prefetch = 0;      // the k-th prefetch uses slot k % n_slots (ring order)
+
+    int find(int layer, SlotState st) const
+    {
+        // oldest first: start at the slot the ring will reuse next
+        for (int i = 0; i < n_slots; ++i) {
+            int s = (int)((n_prefetch + i) % n_slots);
+            if (slots[s].state == st && slots[s].layer == layer) return s;
+        }
+        return -1;
+    }
 };
 
 using tpi::fail;
@@ -87,19 +98,21 @@ int tpi_window_prefetch(tpi_window *w, int32_t layer)
 {
     if (!w) return fail(TPI_EINVAL, "window is null");
     if (layer < 0 || layer >= w->n_layers) return fail(TPI_EINVAL, "layer %d outside [0, %d)", layer, w->n_layers);
-    Slot &s = w->slots[layer % w->n_slots];
+    const int si = (int)(w->n_prefetch % w->n_slots);
+    Slot &s = w->slots[si];
     if (s.state == kPrefetched || s.state == kAcquired)
-        return fail(TPI_ESTATE, "prefetch of layer %d: slot %d still holds layer %d (%s)", layer, layer % w->n_slots,
+        return fail(TPI_ESTATE, "prefetch of layer %d: the window is full, slot %d still holds layer %d (%s)", layer, si,
                     s.layer, s.state == kAcquired ? "acquired, not released" : "prefetched, not yet used");
     // the previous tenant's readers must have finished before the copy lands
     if (s.state == kReleased) TPI_HIP(hipStreamWaitEvent(w->copy, s.freed, 0));
     if (!w->any_copy) TPI_HIP(hipEventRecord(w->first_begin, w->copy));
-    TPI_HIP(hipMemcpyAsync(w->slots_base + (size_t)(layer % w->n_slots) * w->layer_bytes, w->blobs[layer],
-                           w->layer_bytes, hipMemcpyHostToDevice, w->copy));
+    TPI_HIP(hipMemcpyAsync(w->slots_base + (size_t)si * w->layer_bytes, w->blobs[layer], w->layer_bytes,
+                           hipMemcpyHostToDevice, w->copy));
     TPI_HIP(hipEventRecord(s.ready, w->copy));
     TPI_HIP(hipEventRecord(w->last_done, w->copy));
     w->any_copy = true;
     w->bytes_copied += w->layer_bytes;
+    w->n_prefetch += 1;
     s.layer = layer;
     s.state = kPrefetched;
     return TPI_OK;
@@ -109,13 +122,12 @@ int tpi_window_acquire(tpi_window *w, int32_t layer, void *compute_stream, const
 {
     if (!w || !dev_blob) return fail(TPI_EINVAL, "null argument");
     if (layer < 0 || layer >= w->n_layers) return fail(TPI_EINVAL, "layer %d outside [0, %d)", layer, w->n_layers);
-    Slot &s = w->slots[layer % w->n_slots];
-    if (s.state != kPrefetched || s.layer != layer)
-        return fail(TPI_ESTATE, "acquire of layer %d: it is not the prefetched tenant of slot %d", layer,
-                    layer % w->n_slots);
+    const int si = w->find(layer, kPrefetched);
+    if (si < 0) return fail(TPI_ESTATE, "acquire of layer %d: no prefetched copy of it is in the window", layer);
+    Slot &s = w->slots[si];
     TPI_HIP(hipStreamWaitEvent((hipStream_t)compute_stream, s.ready, 0));
     s.state = kAcquired;
-    *dev_blob = w->slots_base + (size_t)(layer % w->n_slots) * w->layer_bytes;
+    *dev_blob = w->slots_base + (size_t)si * w->layer_bytes;
     return TPI_OK;
 }
 
@@ -123,9 +135,9 @@ int tpi_window_release(tpi_window *w, int32_t layer, void *compute_stream)
 {
     if (!w) return fail(TPI_EINVAL, "window is null");
     if (layer < 0 || layer >= w->n_layers) return fail(TPI_EINVAL, "layer %d outside [0, %d)", layer, w->n_layers);
-    Slot &s = w->slots[layer % w->n_slots];
-    if (s.state != kAcquired || s.layer != layer)
-        return fail(TPI_ESTATE, "release of layer %d: it was not acquired", layer);
+    const int si = w->find(layer, kAcquired);
+    if (si < 0) return fail(TPI_ESTATE, "release of layer %d: it was not acquired", layer);
+    Slot &s = w->slots[si];
     TPI_HIP(hipEventRecord(s.freed, (hipStream_t)compute_stream));
     s.state = kReleased;
     return TPI_OK;

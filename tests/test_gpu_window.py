@@ -1,0 +1,157 @@
+"""Sliding weight window on the GPU: a windowed run must equal the resident run
+bit for bit, and protocol violations must be reported, not executed."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_00531_amd import binding as B
+from paper_2410_00531_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _blob_views(base_ptr, layout):
+    w = B.tpi_layer_weights()
+    for name, (off, _, _) in layout.items():
+        setattr(w, name, base_ptr + off * 4)
+    return w
+
+
+def _layout(h, nq, nkv, d, sl):
+    shapes = synth.shard_tensor_shapes(h, nq, nkv, d, sl)
+    off, out = 0, {}
+    for name in synth.TENSOR_ORDER:
+        n = int(np.prod(shapes[name]))
+        out[name] = (off, shapes[name], n)
+        off += n
+    return out, off
+
+
+def _run_tokens(cfg, L, n_tokens, pos0, h0, kv, get_layer, release_layer):
+    """Decode n_tokens through L layers of ONE shard (N = 1 reduce adds the shortcut)."""
+    x = h0.clone()
+    part = torch.empty_like(x); h_attn = torch.empty_like(x); out = torch.empty_like(x)
+    ws = torch.empty(B.tpi_workspace_bytes(cfg, 1) // 4, device="cuda")
+    outs = []
+    for t in range(n_tokens):
+        src = x
+        for l in range(L):
+            w = get_layer(l)
+            B.tpi_shard_layer_decode(cfg, w, kv[l], pos0 + t, B.TPI_PHASE_ATTN, src, part, ws)
+            B.tpi_star_reduce([part], src, h_attn)
+            B.tpi_shard_layer_decode(cfg, w, None, pos0 + t, B.TPI_PHASE_FFN, h_attn, part, ws)
+            B.tpi_star_reduce([part], h_attn, out)
+            release_layer(l)
+            src = out.clone()
+        outs.append(src.clone())
+    torch.cuda.synchronize()
+    return outs
+
+
+@pytest.mark.parametrize("L,W", [(6, 2), (5, 4), (4, 1), (3, 3)])
+def test_windowed_run_equals_resident_run_bitwise(L, W):
+    h, nq, nkv, d, sl = 512, 4, 2, 64, 1024
+    pos0, n_tokens, max_seq = 9, 3, 16
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq)
+    layout, nfl = _layout(h, nq, nkv, d, sl)
+    rng = np.random.default_rng(L * 10 + W)
+    host = []
+    for l in range(L):
+        w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+        blob = torch.empty(nfl, dtype=torch.float32).pin_memory()
+        for name, (off, _, n) in layout.items():
+            blob[off:off + n] = torch.from_numpy(w[name].reshape(-1))
+        host.append(blob)
+    h0 = torch.from_numpy(rng.standard_normal(h).astype(np.float32)).cuda()
+
+    def fresh_kv():
+        g = torch.Generator(device="cuda"); g.manual_seed(5)
+        caches = []
+        for l in range(L):
+            K = torch.zeros((nkv, max_seq, d), device="cuda"); V = torch.zeros_like(K)
+            K[:, :pos0] = torch.randn((nkv, pos0, d), generator=g, device="cuda")
+            V[:, :pos0] = torch.randn((nkv, pos0, d), generator=g, device="cuda")
+            caches.append((K, V))
+        return caches, [B.make_kv(K, V) for K, V in caches]
+
+    # resident
+    dev_blobs = [b.cuda() for b in host]
+    _, kv = fresh_kv()
+    ref = _run_tokens(cfg, L, n_tokens, pos0, h0, kv,
+                      lambda l: _blob_views(dev_blobs[l].data_ptr(), layout), lambda l: None)
+    # windowed
+    slots = torch.empty(W * nfl, dtype=torch.float32, device="cuda")
+    win = B.Window(host, slots, W, nfl * 4)
+    for l in range(min(W, L)):
+        win.prefetch(l)
+    keep, kv = fresh_kv()
+    issued = [min(W, L)]          # layers prefetched so far, counted cyclically over tokens
+    total = L * n_tokens
+
+    def get_layer(l):
+        return _blob_views(win.acquire(l), layout)
+
+    def release_layer(l):
+        win.release(l)
+        if issued[0] < total:
+            win.prefetch(issued[0] % L)
+            issued[0] += 1
+
+    got = _run_tokens(cfg, L, n_tokens, pos0, h0, kv, get_layer, release_layer)
+    ms, nbytes = win.copy_stats()
+    assert nbytes == total * nfl * 4 and ms > 0
+    win.destroy()
+    for a, b in zip(got, ref):
+        assert torch.equal(a, b)
+
+
+def test_window_protocol_errors():
+    nfl = 1024
+    host = [torch.zeros(nfl).pin_memory() for _ in range(4)]
+    slots = torch.empty(2 * nfl, device="cuda")
+    win = B.Window(host, slots, 2, nfl * 4)
+
+    def code(fn, *a):
+        with pytest.raises(B.TpiError) as ei:
+            fn(*a)
+        return ei.value.code
+
+    assert code(win.acquire, 0) == B.TPI_ESTATE            # never prefetched
+    assert code(win.release, 0) == B.TPI_ESTATE
+    assert code(win.prefetch, 4) == B.TPI_EINVAL
+    assert code(win.prefetch, -1) == B.TPI_EINVAL
+    win.prefetch(0)                                        # ring slot 0
+    win.prefetch(1)                                        # ring slot 1
+    assert code(win.prefetch, 2) == B.TPI_ESTATE           # window full: slot 0's tenant not used yet
+    assert "full" in B.tpi_last_error()
+    assert code(win.acquire, 2) == B.TPI_ESTATE            # not in the window
+    p0 = win.acquire(0); p1 = win.acquire(1)
+    assert p0 == slots.data_ptr() and p1 == slots.data_ptr() + nfl * 4
+    assert code(win.acquire, 0) == B.TPI_ESTATE            # twice
+    assert code(win.prefetch, 2) == B.TPI_ESTATE           # acquired, not released
+    assert code(win.release, 2) == B.TPI_ESTATE
+    win.release(0)
+    assert code(win.release, 0) == B.TPI_ESTATE
+    win.prefetch(2)                                        # slot 0 is free again
+    assert win.acquire(2) == p0
+    assert code(win.prefetch, 3) == B.TPI_ESTATE           # next ring slot (1) still acquired
+    win.release(2); win.release(1)
+    win.prefetch(3)
+    assert win.acquire(3) == p1
+    win.release(3)
+    win.destroy()
+
+
+def test_window_copy_lands_in_the_right_slot():
+    nfl = 4096
+    host = [torch.full((nfl,), float(l + 1)).pin_memory() for l in range(5)]
+    slots = torch.zeros(3 * nfl, device="cuda")
+    win = B.Window(host, slots, 3, nfl * 4)
+    for l in range(5):
+        win.prefetch(l)
+        ptr = win.acquire(l)
+        assert ptr == slots.data_ptr() + (l % 3) * nfl * 4
+        torch.cuda.current_stream().synchronize()          # the stream waited for the copy
+        assert (slots[(l % 3) * nfl:(l % 3 + 1) * nfl] == float(l + 1)).all()
+        win.release(l)
+    win.destroy()
