@@ -42,6 +42,9 @@ def parse():
                     help="all: only the 8-shard emulated job; one: only one device's shard; both (default)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference row for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--no-window", action="store_true", help="skip the windowed-weights leg")
+    ap.add_argument("--window-layers", type=int, default=4)
+    ap.add_argument("--window-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
     ap.add_argument("--seed", type=int, default=0)
@@ -82,6 +85,91 @@ def token_bytes(m, n_shards, n_reduce, n_layers, pos):
     sb = stage_bytes(m, n_shards, pos)
     reduce_b = (n_reduce + 2) * m.hidden * 4          # N partials + shortcut read, one write
     return n_layers * (sum(sb.values()) + 2 * reduce_b)
+
+
+def window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_one, WS_one, h0, h_a, h_b, h_attn,
+               pos0, ms_resident):
+    """Shard 0 again, but its layer blobs live in pinned host memory and pass through a ring of
+    --window-layers HBM slots, refilled by async copies while earlier layers compute."""
+    import torch
+
+    from paper_2410_00531_amd import binding as B
+    from paper_2410_00531_amd import synth
+    dev = h0.device
+    Wn = min(args.window_layers, L)
+    nbytes = blob_floats * 4
+    host = []
+    for l in range(L):
+        hb = torch.empty(blob_floats, dtype=torch.float32, pin_memory=True)
+        hb.copy_(blobs[l][0])
+        host.append(hb)
+    slots = torch.empty(Wn * blob_floats, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    # practical peak of the link: plain pinned host-to-device copies of one blob
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 8
+    slots[:blob_floats].copy_(host[0], non_blocking=True)
+    e0.record()
+    for i in range(reps):
+        slots[:blob_floats].copy_(host[i % L], non_blocking=True)
+    e1.record(); torch.cuda.synchronize()
+    link_gbps = reps * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    lib = B.lib()
+    stream = torch.cuda.current_stream().cuda_stream
+    cfg_p = C.byref(cfg)
+    by_ptr = {}
+    for s_i in range(Wn):
+        w = (B.tpi_layer_weights * 1)()
+        base = slots.data_ptr() + s_i * nbytes
+        for name in synth.TENSOR_ORDER:
+            setattr(w[0], name, base + layout[name][0] * 4)
+        by_ptr[base] = w
+    win = B.Window(host, slots, Wn, nbytes)
+    for l in range(Wn):
+        win.prefetch(l)
+    nxt = [Wn]
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(B.tpi_last_error())
+
+    def token(pos):
+        src, dst = h0, h_a
+        for l in range(L):
+            w = by_ptr[win.acquire(l)]
+            check(lib.tpi_shards_layer_decode(cfg_p, 1, w, KV_one[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
+                                              P_one, WS_one, stream))
+            check(lib.tpi_star_reduce(P_all, N, m.hidden, src.data_ptr(), h_attn.data_ptr(), stream))
+            check(lib.tpi_shards_layer_decode(cfg_p, 1, w, None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
+                                              P_one, WS_one, stream))
+            check(lib.tpi_star_reduce(P_all, N, m.hidden, h_attn.data_ptr(), dst.data_ptr(), stream))
+            win.release(l)
+            win.prefetch(nxt[0] % L)            # slides on into the next token's layers
+            nxt[0] += 1
+            src, dst = dst, (h_b if dst is h_a else h_a)
+        return src
+
+    token(pos0)                                  # warm-up token (the first window was preloaded)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for i in range(args.window_steps):
+        out = token(pos0 + 1 + i)
+    torch.cuda.current_stream().synchronize()
+    ms = (time.perf_counter() - t) * 1e3 / args.window_steps
+    finite = bool(torch.isfinite(out).all().item())
+    win.destroy()
+    copy_ms = L * nbytes / (link_gbps * 1e9) * 1e3
+    return {
+        "workload": f"{m.name}-windowed-decode-one-shard", "window_layers": Wn, "steps": args.window_steps,
+        "ms_per_token": round(ms, 2), "tokens_per_s": round(1e3 / ms, 3),
+        "h2d_gb_per_token": round(L * nbytes / 1e9, 3), "pcie_gbps": round(L * nbytes / (ms * 1e-3) / 1e9, 2),
+        "link_peak_gbps_plain_copy": round(link_gbps, 2),
+        "pcie_frac_of_plain_copy": round(L * nbytes / (ms * 1e-3) / 1e9 / link_gbps, 4),
+        "copy_ms_per_token_at_link_peak": round(copy_ms, 2), "resident_ms_per_token": round(ms_resident, 3),
+        "hidden_fraction": round(1.0 - (ms - ms_resident) / copy_ms, 4),
+        "compute_over_copy": round(ms_resident / copy_ms, 4), "output_finite": finite,
+    }
 
 
 def main():
@@ -272,6 +360,12 @@ def main():
         "output_finite": finite,
         "setup_s": round(setup_s, 1),
     }
+
+    # ---- one shard with its weights streamed through a sliding window (pinned host -> HBM) --------
+    if not args.no_window and args.mode in ("both", "one"):
+        result["window"] = window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_one, WS_one,
+                                      h0, h_a, h_b, h_attn, kv_len + n_tokens_total - args.window_steps - 2,
+                                      ms_one)
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample ------------------------------
     if not args.no_cpu_baseline:
