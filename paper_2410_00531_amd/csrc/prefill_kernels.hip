@@ -1,16 +1,462 @@
-// bf16 prefill path -- not built yet: the entry point reports TPI_EUNSUPPORTED.
+// bf16 prefill of one shard's decoder layer on gfx950: the GEMMs run on the
+// matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation), the small
+// element-wise steps and the causal attention run on the vector ALUs.
+//
+// ATTN phase: k_rmsnorm_bf16 -> gemm (QKV) -> k_rope_scatter (rotary, cache fill)
+//             -> k_prefill_attn (causal GQA attention) -> gemm (output projection)
+// FFN phase:  k_rmsnorm_bf16 -> gemm (gate | up) -> k_swiglu -> gemm (down projection)
 #include "prefill.hpp"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
 
 #include "host_util.hpp"
 
 namespace tpi {
 
-size_t prefill_workspace_bytes(const tpi_shard_cfg *, int32_t) { return 0; }
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef unsigned short bf16_t;   // storage type
 
-int prefill_launch(const tpi_shard_cfg *, const tpi_layer_weights *, const tpi_kv_layer *, int32_t, int32_t, int,
-                   const void *, float *, void *, hipStream_t)
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((unsigned)v << 16); }
+
+// round to nearest, ties to even
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
 {
-    return fail(TPI_EUNSUPPORTED, "prefill kernels are not built in this version");
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float wsum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// RMSNorm of n tokens: out[t][k] = bf16( x[t][k] / sqrt(mean_k x^2 + eps) * g[k] ).  One workgroup per token.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_rmsnorm_bf16(const bf16_t *__restrict__ x, const float *__restrict__ g,
+                                                      bf16_t *__restrict__ out, int h, float eps)
+{
+    __shared__ float red[4];
+    const bf16_t *xr = x + (size_t)blockIdx.x * h;
+    bf16_t *orow = out + (size_t)blockIdx.x * h;
+    float ss = 0.f;
+    for (int k = threadIdx.x * 8; k < h; k += 256 * 8) {
+        uint4 raw = *reinterpret_cast<const uint4 *>(xr + k);
+        const bf16_t *e = reinterpret_cast<const bf16_t *>(&raw);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { float v = bf16_to_f32(e[i]); ss = fmaf(v, v, ss); }
+    }
+    ss = wsum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)h + eps);
+    for (int k = threadIdx.x * 8; k < h; k += 256 * 8) {
+        uint4 raw = *reinterpret_cast<const uint4 *>(xr + k);
+        const bf16_t *e = reinterpret_cast<const bf16_t *>(&raw);
+        float4 g0 = *reinterpret_cast<const float4 *>(g + k), g1 = *reinterpret_cast<const float4 *>(g + k + 4);
+        const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+        uint4 o;
+        bf16_t *oe = reinterpret_cast<bf16_t *>(&o);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) oe[i] = f32_to_bf16(bf16_to_f32(e[i]) * rinv * gg[i]);
+        *reinterpret_cast<uint4 *>(orow + k) = o;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// C[m][n] = sum_k A[m][k] * B[n][k]   (bf16 in, fp32 out; both operands K-contiguous)
+// ---------------------------------------------------------------------------
+// Rows n < n_split of B come from B0, the rest from B1 (gate | up share one launch).
+// Workgroup tile BM x BN, 4 waves as 2 x 2, each wave (BM/2) x (BN/2) in 32x32 MFMA
+// tiles; K advances in steps of 64 through LDS (rows padded by 8 elements so the
+// 16-byte fragment reads of 8 consecutive lanes fall into distinct bank groups),
+// the next K-step's global loads are in flight while the current one is multiplied.
+struct GemmArgs {
+    const bf16_t *A;
+    const bf16_t *B0, *B1;
+    float *C;
+    int M, N, K, n_split;
+    int lda, ldb, ldc;
+};
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void k_gemm_bf16_nt(GemmArgs g)
+{
+    constexpr int BK = 64, LDT = BK + 8;
+    constexpr int MI = BM / 64, NI = BN / 64;           // 32x32 tiles per wave along m and n
+    constexpr int ACH = BM * (BK / 8) / 256;            // 16-byte chunks per thread, A tile
+    constexpr int BCH = BN * (BK / 8) / 256;
+    __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDT];
+    __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDT];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    uint4 ra[ACH], rb[BCH];
+    auto load_tiles = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) {
+            int c = tid + i * 256, row = c >> 3, kc = (c & 7) * 8;
+            int m = m0 + row, k = k0 + kc;
+            ra[i] = (m < g.M && k < g.K) ? *reinterpret_cast<const uint4 *>(g.A + (size_t)m * g.lda + k)
+                                         : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < BCH; ++i) {
+            int c = tid + i * 256, row = c >> 3, kc = (c & 7) * 8;
+            int n = n0 + row, k = k0 + kc;
+            const bf16_t *src = (n < g.n_split) ? g.B0 + (size_t)n * g.ldb : g.B1 + (size_t)(n - g.n_split) * g.ldb;
+            rb[i] = (n < g.N && k < g.K) ? *reinterpret_cast<const uint4 *>(src + k) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_tiles = [&]() {
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) {
+            int c = tid + i * 256, row = c >> 3, kc = (c & 7) * 8;
+            *reinterpret_cast<uint4 *>(As + row * LDT + kc) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < BCH; ++i) {
+            int c = tid + i * 256, row = c >> 3, kc = (c & 7) * 8;
+            *reinterpret_cast<uint4 *>(Bs + row * LDT + kc) = rb[i];
+        }
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int a = 0; a < MI; ++a)
+#pragma unroll
+        for (int b = 0; b < NI; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    load_tiles(0);
+    for (int k0 = 0; k0 < g.K; k0 += BK) {
+        store_tiles();
+        __syncthreads();
+        if (k0 + BK < g.K) load_tiles(k0 + BK);
+        const int fr = lane & 31, fk = (lane >> 5) * 8;
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            bf16x8 fa[MI], fb[NI];
+#pragma unroll
+            for (int a = 0; a < MI; ++a)
+                fa[a] = *reinterpret_cast<const bf16x8 *>(As + (wm * (BM / 2) + a * 32 + fr) * LDT + s * 16 + fk);
+#pragma unroll
+            for (int b = 0; b < NI; ++b)
+                fb[b] = *reinterpret_cast<const bf16x8 *>(Bs + (wn * (BN / 2) + b * 32 + fr) * LDT + s * 16 + fk);
+#pragma unroll
+            for (int a = 0; a < MI; ++a)
+#pragma unroll
+                for (int b = 0; b < NI; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // accumulator register r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of its 32x32 tile
+#pragma unroll
+    for (int a = 0; a < MI; ++a)
+#pragma unroll
+        for (int b = 0; b < NI; ++b) {
+            int col = n0 + wn * (BN / 2) + b * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (row < g.M && col < g.N) g.C[(size_t)row * g.ldc + col] = acc[a][b][r];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------
+// Rotary embedding + cache fill from the fp32 QKV product
+// ---------------------------------------------------------------------------
+// One thread per (token, pair index e): rotates element pair (e, e + d/2) of every query and key head at
+// position pos0 + token (angle in fp64), writes q as bf16 [n][nq*d], K and V into cache slot pos0 + token.
+__global__ __launch_bounds__(256) void k_rope_scatter(const float *__restrict__ qkv, bf16_t *__restrict__ q_out,
+                                                      bf16_t *__restrict__ Kc, bf16_t *__restrict__ Vc, int n, int nq,
+                                                      int nkv, int d, int max_seq, int pos0, double log2_base)
+{
+    const int half = d / 2;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n * half) return;
+    const int t = idx / half, e = idx - t * half;
+    const int pos = pos0 + t;
+    float cs = 1.f, sn = 0.f;
+    if (pos != 0) {
+        double theta = exp2(-(2.0 * (double)e / (double)d) * log2_base);
+        double sd, cd;
+        sincos((double)pos * theta, &sd, &cd);
+        cs = (float)cd;
+        sn = (float)sd;
+    }
+    const int ld = (nq + 2 * nkv) * d;
+    const float *row = qkv + (size_t)t * ld;
+    for (int hd = 0; hd < nq; ++hd) {
+        float lo = row[hd * d + e], hi = row[hd * d + e + half];
+        q_out[(size_t)t * nq * d + hd * d + e] = f32_to_bf16(lo * cs - hi * sn);
+        q_out[(size_t)t * nq * d + hd * d + e + half] = f32_to_bf16(hi * cs + lo * sn);
+    }
+    for (int gk = 0; gk < nkv; ++gk) {
+        float lo = row[(nq + gk) * d + e], hi = row[(nq + gk) * d + e + half];
+        size_t slot = ((size_t)gk * max_seq + pos) * d;
+        Kc[slot + e] = f32_to_bf16(lo * cs - hi * sn);
+        Kc[slot + e + half] = f32_to_bf16(hi * cs + lo * sn);
+        Vc[slot + e] = f32_to_bf16(row[(nq + nkv + gk) * d + e]);
+        Vc[slot + e + half] = f32_to_bf16(row[(nq + nkv + gk) * d + e + half]);
+    }
+}
+
+// act[t][j] = bf16( silu(gu[t][j]) * gu[t][sl + j] )
+__global__ __launch_bounds__(256) void k_swiglu(const float *__restrict__ gu, bf16_t *__restrict__ act, int n, int sl)
+{
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)n * sl) return;
+    const size_t t = idx / sl, j = idx - t * sl;
+    float gt = gu[t * 2 * sl + j], up = gu[t * 2 * sl + sl + j];
+    act[idx] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+}
+
+// ---------------------------------------------------------------------------
+// Causal GQA attention over the bf16 cache (vector ALUs, fp32 arithmetic)
+// ---------------------------------------------------------------------------
+// One workgroup = one KV head x QT consecutive tokens; its rows are the (token, query head of the group)
+// pairs, R = QT * G <= 64.  Keys and values pass through LDS in tiles of 64 slots; thread (r, c) with
+// r = tid / 4 (row) and c = tid % 4 owns the scores of row r against slots c, c+4, ... of the tile and a
+// quarter of the row's output vector; the running softmax state of a row lives in the registers of its 4
+// threads.  Token i attends to slots 0 .. pos0 + i.
+template <int DMAX>
+__global__ __launch_bounds__(256) void k_prefill_attn(const bf16_t *__restrict__ q, const bf16_t *__restrict__ Kc,
+                                                      const bf16_t *__restrict__ Vc, bf16_t *__restrict__ o, int n,
+                                                      int nq, int nkv, int d, int max_seq, int pos0, int QT)
+{
+    constexpr int TK = 64;
+    constexpr int DQ = DMAX / 4;                       // output elements per thread
+    extern __shared__ float smem[];
+    float *Ks = smem;                                  // [TK][d + 1]
+    float *Vs = Ks + TK * (d + 1);                     // [TK][d]
+    float *Qs = Vs + TK * d;                           // [64][d + 1]
+    float *Ps = Qs + 64 * (d + 1);                     // [64][TK + 1]
+
+    const int G = nq / nkv;
+    const int gk = blockIdx.y;
+    const int t_first = blockIdx.x * QT;
+    const int tid = threadIdx.x, r = tid >> 2, c = tid & 3;
+    const int R = QT * G;
+    const int tok = t_first + r / G, hd = gk * G + r % G;
+    const bool row_ok = r < R && tok < n;
+    const float scale = 1.0f / sqrtf((float)d);
+
+    for (int i = tid; i < 64 * d; i += 256) {
+        int rr = i / d, e = i - rr * d;
+        int tk = t_first + rr / G, hh = gk * G + rr % G;
+        float v = 0.f;
+        if (rr < R && tk < n) v = bf16_to_f32(q[(size_t)tk * nq * d + (size_t)hh * d + e]) * scale;
+        Qs[rr * (d + 1) + e] = v;
+    }
+    float m_run = -INFINITY, l_run = 0.f;
+    float acc[DQ];
+#pragma unroll
+    for (int i = 0; i < DQ; ++i) acc[i] = 0.f;
+    const int last_tok = min(t_first + QT, n) - 1;
+    const int n_keys = pos0 + last_tok + 1;            // slots any row of this workgroup may see
+    const int my_last = pos0 + tok;                    // last slot this row sees
+    const bf16_t *Kg = Kc + (size_t)gk * max_seq * d;
+    const bf16_t *Vg = Vc + (size_t)gk * max_seq * d;
+    const int dq4 = d / 4;                             // elements of the output this thread owns: [c*dq4, (c+1)*dq4)
+
+    for (int k0 = 0; k0 < n_keys; k0 += TK) {
+        __syncthreads();
+        for (int i = tid; i < TK * d; i += 256) {
+            int s = i / d, e = i - s * d;
+            bool ok = k0 + s < n_keys;
+            Ks[s * (d + 1) + e] = ok ? bf16_to_f32(Kg[(size_t)(k0 + s) * d + e]) : 0.f;
+            Vs[s * d + e] = ok ? bf16_to_f32(Vg[(size_t)(k0 + s) * d + e]) : 0.f;
+        }
+        __syncthreads();
+        // scores of this row against slots c, c+4, ...
+        float sc[TK / 4];
+#pragma unroll
+        for (int j = 0; j < TK / 4; ++j) sc[j] = 0.f;
+        for (int e = 0; e < d; ++e) {
+            float qv = Qs[r * (d + 1) + e];
+#pragma unroll
+            for (int j = 0; j < TK / 4; ++j) sc[j] = fmaf(qv, Ks[(c + 4 * j) * (d + 1) + e], sc[j]);
+        }
+        float mt = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < TK / 4; ++j) {
+            int slot = k0 + c + 4 * j;
+            if (!row_ok || slot > my_last) sc[j] = -INFINITY;
+            mt = fmaxf(mt, sc[j]);
+        }
+        mt = fmaxf(mt, __shfl_xor(mt, 1, 64));
+        mt = fmaxf(mt, __shfl_xor(mt, 2, 64));
+        const float m_new = fmaxf(m_run, mt);
+        float ls = 0.f;
+#pragma unroll
+        for (int j = 0; j < TK / 4; ++j) {
+            float p = (sc[j] == -INFINITY) ? 0.f : expf(sc[j] - m_new);
+            ls += p;
+            Ps[r * (TK + 1) + c + 4 * j] = p;
+        }
+        ls += __shfl_xor(ls, 1, 64);
+        ls += __shfl_xor(ls, 2, 64);
+        const float alpha = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
+        l_run = l_run * alpha + ls;
+        m_run = (m_new == -INFINITY) ? m_run : m_new;
+#pragma unroll
+        for (int i = 0; i < DQ; ++i) acc[i] *= alpha;
+        __syncthreads();                               // a row's P entries come from its 4 threads
+        for (int s = 0; s < TK; ++s) {
+            float p = Ps[r * (TK + 1) + s];
+#pragma unroll
+            for (int i = 0; i < DQ; ++i)
+                if (i < dq4) acc[i] = fmaf(p, Vs[s * d + c * dq4 + i], acc[i]);
+        }
+    }
+    if (row_ok) {
+        const float inv = 1.0f / l_run;
+#pragma unroll
+        for (int i = 0; i < DQ; ++i)
+            if (i < dq4) o[(size_t)tok * nq * d + (size_t)hd * d + c * dq4 + i] = f32_to_bf16(acc[i] * inv);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+namespace {
+
+struct PrefillLayout {
+    size_t xn, big, q, o, act, total;   // byte offsets
+};
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
+{
+    PrefillLayout L;
+    const size_t dq = (size_t)c->n_q_local * c->head_dim, dkv = (size_t)c->n_kv_local * c->head_dim;
+    size_t off = 0;
+    L.xn = off;  off += align256((size_t)n * c->hidden * 2);
+    size_t qkv = (size_t)n * (dq + 2 * dkv) * 4, gu = (size_t)n * 2 * c->ffn_local * 4;
+    L.big = off; off += align256(qkv > gu ? qkv : gu);
+    L.q = off;   off += align256((size_t)n * dq * 2);
+    L.o = off;   off += align256((size_t)n * dq * 2);
+    L.act = off; off += align256((size_t)n * c->ffn_local * 2);
+    L.total = off;
+    return L;
+}
+
+hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t *B1, int n_split, int ldb, float *C,
+                       int ldc, int M, int N, int K, hipStream_t st)
+{
+    GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc};
+    // full 128x128 tiles when they alone fill the chip twice over, else smaller tiles for more workgroups
+    const long big_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (big_tiles >= 512) {
+        hipLaunchKernelGGL((k_gemm_bf16_nt<128, 128>), dim3((N + 127) / 128, (M + 127) / 128), dim3(256), 0, st, g);
+    } else if ((long)((M + 63) / 64) * ((N + 127) / 128) >= 256) {
+        hipLaunchKernelGGL((k_gemm_bf16_nt<64, 128>), dim3((N + 127) / 128, (M + 63) / 64), dim3(256), 0, st, g);
+    } else {
+        hipLaunchKernelGGL((k_gemm_bf16_nt<64, 64>), dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, g);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t prefill_workspace_bytes(const tpi_shard_cfg *cfg, int32_t n_tokens) { return layout_of(cfg, n_tokens).total; }
+
+int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi_kv_layer *kv, int32_t pos0, int32_t n,
+                   int phase, const void *h_in, float *partial_out, void *workspace, hipStream_t st)
+{
+    const int h = c->hidden, d = c->head_dim, nq = c->n_q_local, nkv = c->n_kv_local, sl = c->ffn_local;
+    const int dq = nq * d, dkv = nkv * d;
+    auto al = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+    if (!al(h_in) || !al(partial_out) || !al(workspace)) return fail(TPI_EUNSUPPORTED, "pointer not 16-byte aligned");
+    const PrefillLayout L = layout_of(c, n);
+    char *ws = static_cast<char *>(workspace);
+    bf16_t *xn = reinterpret_cast<bf16_t *>(ws + L.xn);
+    float *big = reinterpret_cast<float *>(ws + L.big);
+    bf16_t *qb = reinterpret_cast<bf16_t *>(ws + L.q);
+    bf16_t *ob = reinterpret_cast<bf16_t *>(ws + L.o);
+    bf16_t *act = reinterpret_cast<bf16_t *>(ws + L.act);
+    hipError_t e = hipSuccess;
+#define TPI_LAUNCH_OK()                                                                         \
+    do {                                                                                        \
+        e = hipGetLastError();                                                                  \
+        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e)); \
+    } while (0)
+
+    if (phase == TPI_PHASE_ATTN) {
+        if (!w->attn_norm || !w->w_qkv || !w->w_o) return fail(TPI_EINVAL, "null attention weight pointer");
+        if (!al(w->attn_norm) || !al(w->w_qkv) || !al(w->w_o) || !al(kv->k) || !al(kv->v))
+            return fail(TPI_EUNSUPPORTED, "pointer not 16-byte aligned");
+        if (d > 256) return fail(TPI_EUNSUPPORTED, "head_dim %d > 256", d);
+        const int G = nq / nkv;
+        if (G > 64) return fail(TPI_EUNSUPPORTED, "more than 64 query heads per KV head");
+        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n), dim3(256), 0, st, (const bf16_t *)h_in, (const float *)w->attn_norm,
+                           xn, h, c->rms_eps);
+        TPI_LAUNCH_OK();
+        e = launch_gemm(xn, h, (const bf16_t *)w->w_qkv, (const bf16_t *)w->w_qkv, dq + 2 * dkv, h, big, dq + 2 * dkv, n,
+                        dq + 2 * dkv, h, st);
+        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+        const int nthr = n * (d / 2);
+        hipLaunchKernelGGL(k_rope_scatter, dim3((nthr + 255) / 256), dim3(256), 0, st, big, qb, (bf16_t *)kv->k,
+                           (bf16_t *)kv->v, n, nq, nkv, d, c->max_seq, pos0, std::log2((double)c->rope_base));
+        TPI_LAUNCH_OK();
+        const int QT = 64 / G;                         // tokens per workgroup: QT * G <= 64 rows
+        const size_t lds = sizeof(float) * ((size_t)64 * (d + 1) + (size_t)64 * d + (size_t)64 * (d + 1) + 64 * 65);
+        dim3 grid((n + QT - 1) / QT, nkv);
+        if (lds > 65536) {                             // opt in to more than 64 KB of LDS per workgroup
+            int dev = 0, cap = 0;
+            e = hipGetDevice(&dev);
+            if (e == hipSuccess) e = hipDeviceGetAttribute(&cap, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+            if (e != hipSuccess) return fail(TPI_ERUNTIME, "device query failed: %s", hipGetErrorString(e));
+            if ((size_t)cap < lds) return fail(TPI_EUNSUPPORTED, "attention tile needs %zu bytes of LDS, device allows %d", lds, cap);
+            e = (d <= 64) ? hipFuncSetAttribute((const void *)k_prefill_attn<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                          : hipFuncSetAttribute((const void *)k_prefill_attn<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return fail(TPI_ERUNTIME, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+        }
+        if (d <= 64) {
+            hipLaunchKernelGGL((k_prefill_attn<64>), grid, dim3(256), lds, st, qb, (const bf16_t *)kv->k,
+                               (const bf16_t *)kv->v, ob, n, nq, nkv, d, c->max_seq, pos0, QT);
+        } else if (d <= 128) {
+            hipLaunchKernelGGL((k_prefill_attn<128>), grid, dim3(256), lds, st, qb, (const bf16_t *)kv->k,
+                               (const bf16_t *)kv->v, ob, n, nq, nkv, d, c->max_seq, pos0, QT);
+        } else {
+            return fail(TPI_EUNSUPPORTED, "prefill attention is built for head_dim <= 128");
+        }
+        TPI_LAUNCH_OK();
+        e = launch_gemm(ob, dq, (const bf16_t *)w->w_o, (const bf16_t *)w->w_o, h, dq, partial_out, h, n, h, dq, st);
+        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+    } else {
+        if (!w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down) return fail(TPI_EINVAL, "null FFN weight pointer");
+        if (!al(w->ffn_norm) || !al(w->w_gate) || !al(w->w_up) || !al(w->w_down))
+            return fail(TPI_EUNSUPPORTED, "pointer not 16-byte aligned");
+        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n), dim3(256), 0, st, (const bf16_t *)h_in, (const float *)w->ffn_norm,
+                           xn, h, c->rms_eps);
+        TPI_LAUNCH_OK();
+        e = launch_gemm(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, big, 2 * sl, n, 2 * sl, h, st);
+        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+        const size_t tot = (size_t)n * sl;
+        hipLaunchKernelGGL(k_swiglu, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, big, act, n, sl);
+        TPI_LAUNCH_OK();
+        e = launch_gemm(act, sl, (const bf16_t *)w->w_down, (const bf16_t *)w->w_down, h, sl, partial_out, h, n, h, sl, st);
+        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+    }
+#undef TPI_LAUNCH_OK
+    return TPI_OK;
 }
 
 }  // namespace tpi

@@ -1,0 +1,121 @@
+"""GPU parity of the bf16 prefill path (matrix cores) against the CPU oracle.
+Inputs and weights are bf16 values (the oracle gets exactly those, widened);
+tolerance 2e-2 of the oracle output's max-abs; cache slot set is exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tpi_oracle as O
+from paper_2410_00531_amd import binding as B
+from paper_2410_00531_amd import configs, synth
+from tpi_testlib import BF16_TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_t(x_np):
+    """float32 numpy array that already lies on the bf16 grid -> torch bf16 on the GPU (exact)."""
+    return torch.from_numpy(np.ascontiguousarray(x_np)).cuda().to(torch.bfloat16)
+
+
+def _run_prefill_case(h, nq, nkv, d, sl, n, pos0, max_seq, seed, attn_scale=1.0):
+    rng = np.random.default_rng(seed)
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq, dtype=B.TPI_BF16)
+    oc = O.ShardCfg(h, nq, nkv, d, sl, max_seq)
+    w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+    w["w_qkv"] = w["w_qkv"] * attn_scale
+    wb = {k: (v if k.endswith("_norm") else synth.to_bf16_grid(v)) for k, v in w.items()}
+    x = synth.to_bf16_grid(rng.standard_normal((n, h)).astype(np.float32))
+    K = np.zeros((nkv, max_seq, d), np.float32); V = np.zeros_like(K)
+    K[:, :pos0] = synth.to_bf16_grid(rng.standard_normal((nkv, pos0, d)).astype(np.float32))
+    V[:, :pos0] = synth.to_bf16_grid(rng.standard_normal((nkv, pos0, d)).astype(np.float32))
+    sentinel = 123.0
+    K[:, pos0:] = sentinel; V[:, pos0:] = sentinel
+
+    wt = {k: (torch.from_numpy(v).cuda() if k.endswith("_norm") else _bf16_t(v)) for k, v in wb.items()}
+    Kt, Vt = _bf16_t(K), _bf16_t(V)
+    xt = _bf16_t(x)
+    nbytes = B.tpi_workspace_bytes(cfg, n)
+    assert nbytes > 0
+    ws = torch.full((nbytes // 4,), float("nan"), device="cuda")
+    part = torch.empty((n, h), device="cuda")
+    weights = B.make_weights(wt); kv = B.make_kv(Kt, Vt)
+    B.tpi_shard_layer_prefill(cfg, weights, kv, pos0, n, B.TPI_PHASE_ATTN, xt, part, ws)
+    torch.cuda.synchronize()
+    got_attn = part.cpu().numpy().copy()
+    Ko, Vo = K.copy(), V.copy()
+    ref_attn = O.attn_block(oc, wb["attn_norm"], wb["w_qkv"], wb["w_o"], Ko, Vo, pos0, x)
+    e = rel_err(got_attn, ref_attn)
+    assert e <= BF16_TOL, f"attention partial rel err {e:.3e}"
+    Kg, Vg = Kt.float().cpu().numpy(), Vt.float().cpu().numpy()
+    for garr, before, after in ((Kg, K, Ko), (Vg, V, Vo)):
+        changed = (garr != before).any(axis=2)
+        expect = np.zeros_like(changed); expect[:, pos0:pos0 + n] = True
+        assert np.array_equal(changed, expect), "cache slots outside pos0..pos0+n-1 touched, or some not written"
+        assert rel_err(garr[:, pos0:pos0 + n], after[:, pos0:pos0 + n]) <= BF16_TOL
+    # FFN phase on the same input
+    B.tpi_shard_layer_prefill(cfg, weights, None, pos0, n, B.TPI_PHASE_FFN, xt, part, ws)
+    torch.cuda.synchronize()
+    ref_ffn = O.ffn_block(oc, wb["ffn_norm"], wb["w_gate"], wb["w_up"], wb["w_down"], x)
+    e = rel_err(part.cpu().numpy(), ref_ffn)
+    assert e <= BF16_TOL, f"FFN partial rel err {e:.3e}"
+    return got_attn, ref_attn
+
+
+@pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0", [
+    (256, 2, 2, 64, 344, 5, 0),        # tiny shard, a handful of tokens
+    (256, 2, 2, 64, 344, 70, 0),       # more than one 64-token tile
+    (256, 2, 2, 64, 344, 37, 29),      # non-empty cache in front
+    (264, 4, 1, 128, 72, 129, 3),      # K not a multiple of 64, group of 4, ragged everything
+    (512, 8, 1, 128, 256, 64, 0),      # the 70B head layout: 8 query heads on one KV head
+    (128, 3, 3, 32, 64, 200, 0),       # small heads, several key tiles
+])
+def test_prefill_parity_small_shapes(h, nq, nkv, d, sl, n, pos0):
+    _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + 3, seed=h + n + pos0, attn_scale=4.0)
+
+
+def test_prefill_single_token_and_last_slot():
+    _run_prefill_case(256, 2, 2, 64, 344, 1, 0, 1, seed=1)
+    _run_prefill_case(256, 2, 2, 64, 344, 1, 15, 16, seed=2)
+    _run_prefill_case(256, 2, 2, 64, 344, 9, 7, 16, seed=3)
+
+
+def test_prefill_8b_shaped_layer_one_shard():
+    m = configs.LLAMA31_8B_TP4
+    _run_prefill_case(m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local, 128, 0, 128, seed=8)
+
+
+def test_prefill_70b_shaped_layer_one_shard_512_tokens():
+    """BASELINE config 5 shape: 512 prompt tokens, empty cache, one shard of one layer."""
+    m = configs.LLAMA2_70B_TP8
+    _run_prefill_case(m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local, 512, 0, 512, seed=70)
+
+
+def test_prefill_partials_reduce_over_shards():
+    """fp32 partials of 4 emulated shards star-reduced with the shortcut: bit-exact against the
+    oracle's sequential fp32 reduce of the same GPU partials, and within tolerance of the oracle layer."""
+    h, nq, nkv, d, sl, n, N = 256, 2, 1, 64, 128, 48, 4
+    rng = np.random.default_rng(11)
+    cfg = B.make_cfg(h, nq, nkv, d, sl, n, dtype=B.TPI_BF16)
+    oc = O.ShardCfg(h, nq, nkv, d, sl, n)
+    x = synth.to_bf16_grid(rng.standard_normal((n, h)).astype(np.float32))
+    xt = _bf16_t(x)
+    ws = torch.empty(B.tpi_workspace_bytes(cfg, n) // 4, device="cuda")
+    parts, refs = [], []
+    for r in range(N):
+        w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+        wb = {k: (v if k.endswith("_norm") else synth.to_bf16_grid(v)) for k, v in w.items()}
+        wt = {k: (torch.from_numpy(v).cuda() if k.endswith("_norm") else _bf16_t(v)) for k, v in wb.items()}
+        Kt = torch.zeros((nkv, n, d), device="cuda", dtype=torch.bfloat16); Vt = torch.zeros_like(Kt)
+        p = torch.empty((n, h), device="cuda")
+        B.tpi_shard_layer_prefill(cfg, B.make_weights(wt), B.make_kv(Kt, Vt), 0, n, B.TPI_PHASE_ATTN, xt, p, ws)
+        parts.append(p)
+        K = np.zeros((nkv, n, d), np.float32); V = np.zeros_like(K)
+        refs.append(O.attn_block(oc, wb["attn_norm"], wb["w_qkv"], wb["w_o"], K, V, 0, x))
+    res = torch.from_numpy(x).cuda()
+    out = torch.empty((n, h), device="cuda")
+    B.tpi_star_reduce(parts, res, out)
+    torch.cuda.synchronize()
+    want_bits = O.reduce_seq_f32([p.cpu().numpy() for p in parts], x)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), want_bits.view(np.uint32))
+    assert rel_err(out.cpu().numpy(), O.reduce_f64(refs, x)) <= BF16_TOL
