@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--no-window", action="store_true", help="skip the windowed-weights leg")
     ap.add_argument("--window-layers", type=int, default=4)
     ap.add_argument("--window-steps", type=int, default=3)
+    ap.add_argument("--no-prefill", action="store_true", help="skip the bf16 prefill leg")
+    ap.add_argument("--prefill-tokens", type=int, default=512)
+    ap.add_argument("--prefill-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
     ap.add_argument("--seed", type=int, default=0)
@@ -169,6 +172,96 @@ def window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_
         "copy_ms_per_token_at_link_peak": round(copy_ms, 2), "resident_ms_per_token": round(ms_resident, 3),
         "hidden_fraction": round(1.0 - (ms - ms_resident) / copy_ms, 4),
         "compute_over_copy": round(ms_resident / copy_ms, 4), "output_finite": finite,
+    }
+
+
+def prefill_leg(args, m, L, N, seed):
+    """BASELINE config 5: prompt of --prefill-tokens tokens through the whole stack, all N shards emulated,
+    bf16 weights and activations, fp32 partials star-reduced per layer (the reduce also emits the bf16 copy
+    that feeds the next phase)."""
+    import torch
+
+    from paper_2410_00531_amd import binding as B
+    dev = torch.device("cuda:0")
+    n = args.prefill_tokens
+    h, d, sl, nq, nkv = m.hidden, m.head_dim, m.ffn_local, m.nq_local, m.nkv_local
+    dq, dkv = nq * d, nkv * d
+    cfg = B.make_cfg(h, nq, nkv, d, sl, n, m.rms_eps, m.rope_base, dtype=B.TPI_BF16)
+    sizes = [("w_qkv", (dq + 2 * dkv) * h), ("w_o", h * dq), ("w_gate", sl * h), ("w_up", sl * h), ("w_down", h * sl)]
+    blob_elems = sum(s for _, s in sizes)
+    gen = torch.Generator(device=dev); gen.manual_seed(seed + 5)
+    blobs, norms = [], []
+    for l in range(L):
+        b = torch.empty((N, blob_elems), dtype=torch.bfloat16, device=dev)
+        b.normal_(0.0, 0.02, generator=gen)
+        g = torch.empty((N, 2, h), dtype=torch.float32, device=dev).normal_(1.0, 0.02, generator=gen)
+        blobs.append(b); norms.append(g)
+    kc = torch.zeros((L, N, 2, nkv, n, d), dtype=torch.bfloat16, device=dev)
+    x32 = torch.randn((n, h), generator=gen, device=dev)
+    x16 = x32.to(torch.bfloat16)
+    Wl, KVl = [], []
+    for l in range(L):
+        ws_, ks_ = [], []
+        for r in range(N):
+            w = B.tpi_layer_weights()
+            off = blobs[l][r].data_ptr()
+            for name, sz in sizes:
+                setattr(w, name, off); off += sz * 2
+            w.attn_norm = norms[l][r, 0].data_ptr(); w.ffn_norm = norms[l][r, 1].data_ptr()
+            ws_.append(w); ks_.append(B.make_kv(kc[l, r, 0], kc[l, r, 1]))
+        Wl.append(ws_); KVl.append(ks_)
+    ws = torch.empty(B.tpi_workspace_bytes(cfg, n) // 4, dtype=torch.float32, device=dev)
+    parts = torch.empty((N, n, h), dtype=torch.float32, device=dev)
+    P = (C.c_void_p * N)(*[parts[r].data_ptr() for r in range(N)])
+    ha32 = torch.empty_like(x32); ha16 = torch.empty_like(x16)
+    hb32 = torch.empty_like(x32); hb16 = torch.empty_like(x16)
+    lib = B.lib(); stream = torch.cuda.current_stream().cuda_stream; cfg_p = C.byref(cfg)
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(B.tpi_last_error())
+
+    def step():
+        s32, s16 = x32, x16
+        for l in range(L):
+            for r in range(N):
+                check(lib.tpi_shard_layer_prefill(cfg_p, C.byref(Wl[l][r]), C.byref(KVl[l][r]), 0, n,
+                                                  B.TPI_PHASE_ATTN, s16.data_ptr(), parts[r].data_ptr(),
+                                                  ws.data_ptr(), stream))
+            check(lib.tpi_star_reduce_bf16(P, N, n * h, s32.data_ptr(), ha32.data_ptr(), ha16.data_ptr(), stream))
+            for r in range(N):
+                check(lib.tpi_shard_layer_prefill(cfg_p, C.byref(Wl[l][r]), None, 0, n, B.TPI_PHASE_FFN,
+                                                  ha16.data_ptr(), parts[r].data_ptr(), ws.data_ptr(), stream))
+            check(lib.tpi_star_reduce_bf16(P, N, n * h, ha32.data_ptr(), hb32.data_ptr(), hb16.data_ptr(), stream))
+            s32, s16 = hb32, hb16
+        return s32
+
+    step(); torch.cuda.synchronize()
+    K = args.prefill_steps
+    t = time.perf_counter()
+    for _ in range(K):
+        out = step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t) * 1e3 / K
+    B.tpi_prof_enable(B.TPI_STAGE_PREFILL_GEMM, 4 * N * L)
+    step(); torch.cuda.synchronize()
+    gemm_ms, gemm_n = B.tpi_prof_read()
+    B.tpi_prof_enable(B.TPI_STAGE_NONE, 0)
+    gemm_flops = 2.0 * n * (h * (dq + 2 * dkv) + dq * h + 3 * h * sl)
+    attn_flops = 2.0 * nq * d * n * (n + 1)
+    total = (gemm_flops + attn_flops) * N * L
+    peak = 2500.0
+    return {
+        "workload": f"{m.name}-prefill-{n}-tokens", "dtype": "bf16 (fp32 accumulate, fp32 partials)",
+        "layers": L, "shards_emulated": N, "steps": K, "ms_per_prompt": round(ms, 3),
+        "prompt_tokens_per_s": round(n / (ms * 1e-3), 1), "tflop_per_prompt": round(total / 1e12, 2),
+        "tflops": round(total / (ms * 1e-3) / 1e12, 1), "mfma_frac_of_peak_whole_step": round(total / (ms * 1e-3) / 1e12 / peak, 4),
+        "gemm_kernels": {"launches": gemm_n, "total_ms": round(gemm_ms, 3),
+                         "tflops": round(gemm_flops * N * L / (gemm_ms * 1e-3) / 1e12, 1) if gemm_n else None,
+                         "frac_of_bf16_peak": round(gemm_flops * N * L / (gemm_ms * 1e-3) / 1e12 / peak, 4) if gemm_n else None,
+                         "peak_tflops": peak},
+        "reduce_gb_per_prompt": round(2 * L * (N + 2) * n * h * 4 / 1e9 + 2 * L * n * h * 2 / 1e9, 2),
+        "output_finite": bool(torch.isfinite(out).all().item()),
     }
 
 
@@ -390,6 +483,11 @@ def main():
             "sample": f"{reps} x one layer of one shard (attention block + FFN block + one {N}-way reduce) at the "
                       f"workload's shape, {per_layer_shard_ms:.2f} ms each, scaled x{L} layers x{N} shards",
         }
+    # ---- bf16 prefill of the same stack (the fp32 stack is released first: both do not fit) -------
+    if not args.no_prefill and args.mode == "both":
+        del blobs, kc, W_all, KV_all, W_one, KV_one
+        torch.cuda.empty_cache()
+        result["prefill"] = prefill_leg(args, m, L, N, args.seed)
     print(json.dumps(result))
 
 

@@ -157,6 +157,13 @@ int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *h
 int tpi_star_reduce(const float *const *host_partials, int32_t n, int64_t len,
                     const float *residual, float *out, void *stream);
 
+/* The same sum (same bits in `out`); additionally stores the result rounded
+ * to bf16 (nearest, ties to even) in out_bf16 [len]: the fp32 copy stays the
+ * shortcut of the next reduce, the bf16 copy is the h_in of the next prefill
+ * phase.  out_bf16 must not be NULL. */
+int tpi_star_reduce_bf16(const float *const *host_partials, int32_t n, int64_t len,
+                         const float *residual, float *out, void *out_bf16, void *stream);
+
 /*
  * Sliding window of layer shards (Sec. 3.3; appendix "A simple-to-use memory
  * scheduler").  All n_layers blobs live in pinned host memory; `window_layers`
@@ -200,14 +207,14 @@ int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes);
  * Measurement aid (not part of the method): time every launch of one stage
  * with HIP events recorded on the stream the kernel is launched on.
  *   stage: 0 off, 1 QKV+rotary, 2 attention, 3 output projection,
- *          4 gate/up, 5 down projection, 6 star reduce.
+ *          4 gate/up, 5 down projection, 6 star reduce, 7 prefill GEMMs.
  * tpi_prof_enable allocates `capacity` event pairs (launches beyond that are
  * not timed) and clears earlier records; tpi_prof_read waits for the recorded
  * launches, returns the sum of their durations and their count, and clears
  * the records.  Not thread-safe; leave it off in production loops.
  */
 enum { TPI_STAGE_NONE = 0, TPI_STAGE_QKV = 1, TPI_STAGE_ATTN = 2, TPI_STAGE_OPROJ = 3,
-       TPI_STAGE_GATE_UP = 4, TPI_STAGE_DOWN = 5, TPI_STAGE_REDUCE = 6 };
+       TPI_STAGE_GATE_UP = 4, TPI_STAGE_DOWN = 5, TPI_STAGE_REDUCE = 6, TPI_STAGE_PREFILL_GEMM = 7 };
 int tpi_prof_enable(int stage, int32_t capacity);
 int tpi_prof_read(double *total_ms, int32_t *launches);
 

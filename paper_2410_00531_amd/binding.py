@@ -24,12 +24,12 @@ TPI_MAX_BATCH_SHARDS = 16
 
 EXPORTED = (
     "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode",
-    "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_window_create", "tpi_window_prefetch",
+    "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create", "tpi_window_prefetch",
     "tpi_window_acquire", "tpi_window_release", "tpi_window_destroy", "tpi_window_copy_stats",
     "tpi_last_error", "tpi_abi_version", "tpi_prof_enable", "tpi_prof_read",
 )
 TPI_STAGE_NONE, TPI_STAGE_QKV, TPI_STAGE_ATTN, TPI_STAGE_OPROJ = 0, 1, 2, 3
-TPI_STAGE_GATE_UP, TPI_STAGE_DOWN, TPI_STAGE_REDUCE = 4, 5, 6
+TPI_STAGE_GATE_UP, TPI_STAGE_DOWN, TPI_STAGE_REDUCE, TPI_STAGE_PREFILL_GEMM = 4, 5, 6, 7
 
 
 class TpiError(RuntimeError):
@@ -84,6 +84,9 @@ def lib() -> C.CDLL:
         l.tpi_star_reduce.restype = C.c_int
         l.tpi_star_reduce.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p,
                                       C.c_void_p, C.c_void_p]
+        l.tpi_star_reduce_bf16.restype = C.c_int
+        l.tpi_star_reduce_bf16.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p]
         l.tpi_window_create.restype = C.c_int
         l.tpi_window_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_size_t,
                                         C.POINTER(C.c_void_p), C.c_void_p]
@@ -195,6 +198,17 @@ def tpi_star_reduce(partials, residual, out, length: Optional[int] = None, strea
     if length is None:
         length = out.numel()
     _check(lib().tpi_star_reduce(arr, n, length, _ptr(residual), _ptr(out), _stream(stream)))
+
+
+def tpi_star_reduce_bf16(partials, residual, out, out_bf16, length: Optional[int] = None, stream=None) -> None:
+    if isinstance(partials, C.Array):
+        arr, n = partials, len(partials)
+    else:
+        n = len(partials)
+        arr = (C.c_void_p * max(n, 1))(*[_ptr(p) for p in partials])
+    if length is None:
+        length = out.numel()
+    _check(lib().tpi_star_reduce_bf16(arr, n, length, _ptr(residual), _ptr(out), _ptr(out_bf16), _stream(stream)))
 
 
 def tpi_prof_enable(stage: int, capacity: int = 0) -> None:

@@ -12,6 +12,7 @@
 #include <cmath>
 
 #include "host_util.hpp"
+#include "prof.hpp"
 
 namespace tpi {
 
@@ -361,6 +362,7 @@ hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t 
                        int ldc, int M, int N, int K, hipStream_t st)
 {
     GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc};
+    ProfScope ps(kStagePrefillGemm, st);
     // full 128x128 tiles when they alone fill the chip twice over, else smaller tiles for more workgroups
     const long big_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
     if (big_tiles >= 512) {

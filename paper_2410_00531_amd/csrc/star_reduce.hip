@@ -10,6 +10,14 @@ namespace tpi {
 // out[i] = (((p0[i] + p1[i]) + ...) + p_{n-1}[i]) + residual[i]; plain fp32
 // additions in exactly this order (contraction off: there is nothing to fuse,
 // and nothing may be reassociated).
+__device__ __forceinline__ unsigned short to_bf16(float f)
+{
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
 #pragma clang fp contract(off)
 __global__ __launch_bounds__(256) void k_star_reduce(ReduceArgs a)
 {
@@ -26,6 +34,10 @@ __global__ __launch_bounds__(256) void k_star_reduce(ReduceArgs a)
             acc.x = acc.x + v.x; acc.y = acc.y + v.y; acc.z = acc.z + v.z; acc.w = acc.w + v.w;
         }
         reinterpret_cast<float4 *>(a.out)[i] = acc;
+        if (a.out_bf16) {
+            ushort4 b = make_ushort4(to_bf16(acc.x), to_bf16(acc.y), to_bf16(acc.z), to_bf16(acc.w));
+            reinterpret_cast<ushort4 *>(a.out_bf16)[i] = b;
+        }
     }
     // ragged tail (len % 4 elements), or everything when a pointer is not 16-byte aligned
     for (int64_t t = n4 * 4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < a.len; t += stride) {
@@ -33,6 +45,7 @@ __global__ __launch_bounds__(256) void k_star_reduce(ReduceArgs a)
         for (int r = 1; r < a.n; ++r) acc = acc + a.p[r][t];
         if (a.residual) acc = acc + a.residual[t];
         a.out[t] = acc;
+        if (a.out_bf16) a.out_bf16[t] = to_bf16(acc);
     }
 }
 

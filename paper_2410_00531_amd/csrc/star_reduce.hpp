@@ -10,6 +10,7 @@ struct ReduceArgs {
     const float *p[kMaxReduceRanks];
     const float *residual;   // nullable
     float *out;
+    unsigned short *out_bf16;   // nullable: result rounded to bf16 (nearest even)
     int64_t len;
     int n;
     int vec_ok;              // all pointers 16-byte aligned

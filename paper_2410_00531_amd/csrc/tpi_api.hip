@@ -174,8 +174,8 @@ int tpi_shards_layer_decode(const tpi_shard_cfg *cfg, int32_t n_shards, const tp
     return decode_common(cfg, n_shards, host_w, host_kv, pos, phase, h_in, host_partial_out, host_workspace, stream);
 }
 
-int tpi_star_reduce(const float *const *host_partials, int32_t n, int64_t len, const float *residual, float *out,
-                    void *stream)
+static int star_reduce_common(const float *const *host_partials, int32_t n, int64_t len, const float *residual,
+                              float *out, void *out_bf16, void *stream)
 {
     if (!host_partials || !out) return fail(TPI_EINVAL, "null argument");
     if (n < 1) return fail(TPI_EINVAL, "n %d < 1", n);
@@ -183,16 +183,31 @@ int tpi_star_reduce(const float *const *host_partials, int32_t n, int64_t len, c
     if (n > TPI_MAX_REDUCE_RANKS) return fail(TPI_EUNSUPPORTED, "n %d > %d", n, TPI_MAX_REDUCE_RANKS);
     ReduceArgs a;
     std::memset(&a, 0, sizeof(a));
-    bool al = aligned16(out) && (!residual || aligned16(residual));
+    bool al = aligned16(out) && (!residual || aligned16(residual)) &&
+              (!out_bf16 || (reinterpret_cast<uintptr_t>(out_bf16) & 7u) == 0);
     for (int r = 0; r < n; ++r) {
         if (!host_partials[r]) return fail(TPI_EINVAL, "partial %d is null", r);
         a.p[r] = host_partials[r];
         al = al && aligned16(host_partials[r]);
     }
-    a.residual = residual; a.out = out; a.len = len; a.n = n; a.vec_ok = al ? 1 : 0;
+    a.residual = residual; a.out = out; a.out_bf16 = (unsigned short *)out_bf16; a.len = len; a.n = n;
+    a.vec_ok = al ? 1 : 0;
     hipError_t e = launch_star_reduce(a, (hipStream_t)stream);
     if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
     return TPI_OK;
+}
+
+int tpi_star_reduce(const float *const *host_partials, int32_t n, int64_t len, const float *residual, float *out,
+                    void *stream)
+{
+    return star_reduce_common(host_partials, n, len, residual, out, nullptr, stream);
+}
+
+int tpi_star_reduce_bf16(const float *const *host_partials, int32_t n, int64_t len, const float *residual, float *out,
+                         void *out_bf16, void *stream)
+{
+    if (!out_bf16) return fail(TPI_EINVAL, "out_bf16 is null");
+    return star_reduce_common(host_partials, n, len, residual, out, out_bf16, stream);
 }
 
 int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w, const tpi_kv_layer *host_kv,

@@ -119,3 +119,26 @@ def test_prefill_partials_reduce_over_shards():
     want_bits = O.reduce_seq_f32([p.cpu().numpy() for p in parts], x)
     assert np.array_equal(out.cpu().numpy().view(np.uint32), want_bits.view(np.uint32))
     assert rel_err(out.cpu().numpy(), O.reduce_f64(refs, x)) <= BF16_TOL
+
+
+def test_star_reduce_bf16_copy_is_round_to_nearest_even():
+    rng = np.random.default_rng(12)
+    n, length = 5, 4099
+    ps = [(rng.standard_normal(length) * 10 ** rng.uniform(-2, 2, length)).astype(np.float32) for _ in range(n)]
+    res = rng.standard_normal(length).astype(np.float32)
+    tp = [torch.from_numpy(p).cuda() for p in ps]
+    out = torch.empty(length, device="cuda"); out2 = torch.empty(length, device="cuda")
+    ob = torch.empty(length, device="cuda", dtype=torch.bfloat16)
+    B.tpi_star_reduce_bf16(tp, torch.from_numpy(res).cuda(), out, ob)
+    B.tpi_star_reduce(tp, torch.from_numpy(res).cuda(), out2)
+    torch.cuda.synchronize()
+    want = O.reduce_seq_f32(ps, res)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    assert torch.equal(out, out2)
+    assert np.array_equal(ob.float().cpu().numpy(), synth.to_bf16_grid(want))
+    # ties: 1 + 2^-8 lies midway between two bf16 values and must go to the even one (1.0);
+    # 1 + 3*2^-8 midway again, goes up to 1 + 2^-6
+    t = torch.tensor([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 0.0], device="cuda")
+    ob4 = torch.empty(4, device="cuda", dtype=torch.bfloat16); o4 = torch.empty(4, device="cuda")
+    B.tpi_star_reduce_bf16([t], None, o4, ob4); torch.cuda.synchronize()
+    assert ob4.float().tolist() == [1.0, 1.0 + 2.0 ** -6, -1.0, 0.0]
