@@ -204,17 +204,53 @@ int tpi_window_destroy(tpi_window *w);
 int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes);
 
 /*
+ * Whole-token decode of ONE device's shard (Alg. 2, the worker's loop over all
+ * decoder layers of one token) in a single persistent launch: per layer the
+ * attention block, the star reduce with the shortcut, the FFN block and the
+ * second reduce, exactly as the per-phase calls above compute them (bitwise),
+ * but the stages of a layer are separated by barriers inside one co-resident
+ * grid instead of kernel boundaries, and each reduce is folded into the
+ * epilogue of the row-parallel stage before it: this device's partial comes
+ * from registers, the other ranks' partials are read from the buffers given
+ * at creation (the device's receive buffers; entry `rank` of each table is
+ * ignored, n_ranks == 1 needs no tables).
+ *
+ * workspace: tpi_decoder_workspace_bytes() bytes of device memory, 256-byte
+ * aligned, owned by the caller and left to the decoder until destroy.  create
+ * uploads the layer table into it and synchronises `stream` once; token only
+ * enqueues.  Tokens of one decoder must be queued on one stream at a time.
+ * TPI_EUNSUPPORTED: shard shapes the whole-token kernel is not compiled for
+ * (the per-phase calls cover every shape).  If a barrier of the kernel ever
+ * gives up waiting (it is bounded so that the kernel always ends), the run's
+ * output is invalid and tpi_decoder_status() reports TPI_ERUNTIME; status
+ * synchronises the stream.
+ */
+typedef struct tpi_decoder tpi_decoder;
+size_t tpi_decoder_workspace_bytes(const tpi_shard_cfg *cfg, int32_t n_layers);
+int tpi_decoder_create(tpi_decoder **out, const tpi_shard_cfg *cfg, int32_t n_layers,
+                       const tpi_layer_weights *host_w /* [n_layers] */,
+                       const tpi_kv_layer *host_kv /* [n_layers] */, int32_t n_ranks, int32_t rank,
+                       const float *const *host_peer_attn /* [n_ranks] device ptrs to [h] */,
+                       const float *const *host_peer_ffn /* [n_ranks] device ptrs to [h] */,
+                       void *workspace, void *stream);
+int tpi_decoder_token(tpi_decoder *dec, int32_t pos, const float *h_in, float *h_out, void *stream);
+int tpi_decoder_status(tpi_decoder *dec, void *stream);
+int tpi_decoder_grid(const tpi_decoder *dec);   /* workgroups of the persistent grid */
+int tpi_decoder_destroy(tpi_decoder *dec);
+
+/*
  * Measurement aid (not part of the method): time every launch of one stage
  * with HIP events recorded on the stream the kernel is launched on.
  *   stage: 0 off, 1 QKV+rotary, 2 attention, 3 output projection,
- *          4 gate/up, 5 down projection, 6 star reduce, 7 prefill GEMMs.
+ *          4 gate/up, 5 down projection, 6 star reduce, 7 prefill GEMMs,
+ *          8 whole-token kernel.
  * tpi_prof_enable allocates `capacity` event pairs (launches beyond that are
  * not timed) and clears earlier records; tpi_prof_read waits for the recorded
  * launches, returns the sum of their durations and their count, and clears
  * the records.  Not thread-safe; leave it off in production loops.
  */
 enum { TPI_STAGE_NONE = 0, TPI_STAGE_QKV = 1, TPI_STAGE_ATTN = 2, TPI_STAGE_OPROJ = 3,
-       TPI_STAGE_GATE_UP = 4, TPI_STAGE_DOWN = 5, TPI_STAGE_REDUCE = 6, TPI_STAGE_PREFILL_GEMM = 7 };
+       TPI_STAGE_GATE_UP = 4, TPI_STAGE_DOWN = 5, TPI_STAGE_REDUCE = 6, TPI_STAGE_PREFILL_GEMM = 7, TPI_STAGE_TOKEN = 8 };
 int tpi_prof_enable(int stage, int32_t capacity);
 int tpi_prof_read(double *total_ms, int32_t *launches);
 

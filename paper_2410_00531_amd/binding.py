@@ -27,9 +27,12 @@ EXPORTED = (
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create", "tpi_window_prefetch",
     "tpi_window_acquire", "tpi_window_release", "tpi_window_destroy", "tpi_window_copy_stats",
     "tpi_last_error", "tpi_abi_version", "tpi_prof_enable", "tpi_prof_read",
+    "tpi_decoder_workspace_bytes", "tpi_decoder_create", "tpi_decoder_token", "tpi_decoder_status",
+    "tpi_decoder_grid", "tpi_decoder_destroy",
 )
 TPI_STAGE_NONE, TPI_STAGE_QKV, TPI_STAGE_ATTN, TPI_STAGE_OPROJ = 0, 1, 2, 3
 TPI_STAGE_GATE_UP, TPI_STAGE_DOWN, TPI_STAGE_REDUCE, TPI_STAGE_PREFILL_GEMM = 4, 5, 6, 7
+TPI_STAGE_TOKEN = 8
 
 
 class TpiError(RuntimeError):
@@ -105,6 +108,21 @@ def lib() -> C.CDLL:
         l.tpi_prof_enable.argtypes = [C.c_int, C.c_int32]
         l.tpi_prof_read.restype = C.c_int
         l.tpi_prof_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        l.tpi_decoder_workspace_bytes.restype = C.c_size_t
+        l.tpi_decoder_workspace_bytes.argtypes = [C.POINTER(tpi_shard_cfg), C.c_int32]
+        l.tpi_decoder_create.restype = C.c_int
+        l.tpi_decoder_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(tpi_shard_cfg), C.c_int32,
+                                         C.POINTER(tpi_layer_weights), C.POINTER(tpi_kv_layer), C.c_int32,
+                                         C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p,
+                                         C.c_void_p]
+        l.tpi_decoder_token.restype = C.c_int
+        l.tpi_decoder_token.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.tpi_decoder_status.restype = C.c_int
+        l.tpi_decoder_status.argtypes = [C.c_void_p, C.c_void_p]
+        l.tpi_decoder_grid.restype = C.c_int
+        l.tpi_decoder_grid.argtypes = [C.c_void_p]
+        l.tpi_decoder_destroy.restype = C.c_int
+        l.tpi_decoder_destroy.argtypes = [C.c_void_p]
         _lib = l
     return _lib
 
@@ -220,6 +238,54 @@ def tpi_prof_read():
     ms, n = C.c_double(), C.c_int32()
     _check(lib().tpi_prof_read(C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def tpi_decoder_workspace_bytes(cfg: tpi_shard_cfg, n_layers: int) -> int:
+    return int(lib().tpi_decoder_workspace_bytes(C.byref(cfg), n_layers))
+
+
+class Decoder:
+    """tpi_decoder_* as an object: one device's shard, all layers of a token per launch."""
+
+    def __init__(self, cfg, weights: Sequence[tpi_layer_weights], kvs: Sequence[tpi_kv_layer], rank: int = 0,
+                 peer_attn: Optional[Sequence] = None, peer_ffn: Optional[Sequence] = None, stream=None):
+        n = len(weights)
+        self._h = C.c_void_p()
+        nbytes = tpi_decoder_workspace_bytes(cfg, n)
+        if nbytes == 0:
+            raise TpiError(TPI_EINVAL, "bad shard configuration")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        warr = weights if isinstance(weights, C.Array) else (tpi_layer_weights * n)(*weights)
+        karr = kvs if isinstance(kvs, C.Array) else (tpi_kv_layer * n)(*kvs)
+        n_ranks = len(peer_attn) if peer_attn is not None else 1
+        pa = pf = None
+        if n_ranks > 1:
+            pa = (C.c_void_p * n_ranks)(*[_ptr(p) if i != rank else None for i, p in enumerate(peer_attn)])
+            pf = (C.c_void_p * n_ranks)(*[_ptr(p) if i != rank else None for i, p in enumerate(peer_ffn)])
+        self._keep = (weights, kvs, peer_attn, peer_ffn)
+        _check(lib().tpi_decoder_create(C.byref(self._h), C.byref(cfg), n, warr, karr, n_ranks, rank, pa, pf,
+                                        _ptr(self.workspace), _stream(stream)))
+
+    @property
+    def grid(self) -> int:
+        return int(lib().tpi_decoder_grid(self._h))
+
+    def token(self, pos: int, h_in, h_out, stream=None) -> None:
+        _check(lib().tpi_decoder_token(self._h, pos, _ptr(h_in), _ptr(h_out), _stream(stream)))
+
+    def status(self, stream=None) -> None:
+        _check(lib().tpi_decoder_status(self._h, _stream(stream)))
+
+    def destroy(self) -> None:
+        if self._h:
+            h, self._h = self._h, C.c_void_p()
+            _check(lib().tpi_decoder_destroy(h))
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
 
 
 class Window:

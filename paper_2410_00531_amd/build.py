@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtpi.so")
-SOURCES = ["tpi_api.hip", "decode_kernels.hip", "star_reduce.hip", "prefill_kernels.hip", "window.hip", "prof.hip"]
+SOURCES = ["tpi_api.hip", "decode_kernels.hip", "decode_persistent.hip", "star_reduce.hip", "prefill_kernels.hip", "window.hip", "prof.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
@@ -19,9 +19,9 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_lib(verbose: bool = False, extra_flags=()) -> str:
+def build_lib(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -33,7 +33,7 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and err.strip():
         print(err)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -14,9 +14,11 @@ struct ShardView {
     float *k, *v;          // [nkv][max_seq][d]
     float *partial_out;    // [h]
     float *ws;             // workspace base
+    __host__ __device__ unsigned *ws_u32() const { return reinterpret_cast<unsigned *>(ws); }
 };
 
-struct DecodeArgs {
+// Shape, position and workspace layout: everything but the per-shard pointers.
+struct DecodeDims {
     int h, nq, nkv, d, sl, max_seq, pos;
     float eps;
     double log2_base;      // log2(rope_base)
@@ -27,9 +29,23 @@ struct DecodeArgs {
     int ws_att_m;          // [nq][kAttnMaxSplits]      split maxima
     int ws_att_l;          // [nq][kAttnMaxSplits]      split sums
     int ws_att_acc;        // [nq][kAttnMaxSplits][d]   split unnormalised outputs
+    int ws_o;              // [nq*d]                    merged, normalised attention output
     int ws_act;            // [sl]                      silu(gate) * up
+    int ws_cnt;            // [nkv] uint32              attention merge tickets (zeroed by stage 1)
     int ws_total;          // floats
+};
+
+struct DecodeArgs : DecodeDims {
     ShardView s[kMaxBatchShards];
+};
+
+// Star reduce folded into the epilogue of a row-parallel stage (one device's view: its own partial
+// is in registers, the peers' partials are in memory).  out[i] = sum in rank order, then + residual.
+struct FusedReduce {
+    int n = 0, rank = 0;                  // n == 0: no folding, the stage stores its partial
+    const float *const *peer = nullptr;   // device table [n] of partial vectors; entry `rank` is not read
+    const float *residual = nullptr;
+    float *out = nullptr;
 };
 
 hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st);

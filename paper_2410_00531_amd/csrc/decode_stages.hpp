@@ -1,0 +1,447 @@
+// Stage bodies of the fp32 decode path, shared by the per-stage kernels and the
+// whole-token persistent kernel.  (vwg, nvwg): this workgroup's index and the
+// number of workgroups sharing the stage for one shard; units are dealt out
+// cyclically.
+#pragma once
+#include "decode_args.hpp"
+#include "tpi_device.hpp"
+
+namespace tpi {
+
+// RMSNorm folded into a GEMV: xr <- x * g (this thread's slice); returns
+// 1/sqrt(mean(x^2) + eps), which scales the row sums afterwards.
+template <int KCH>
+__device__ __forceinline__ float norm_slice(const float *x, const float *g, int h, float eps, float4 (&xr)[KCH],
+                                            float *red)
+{
+    float4 gr[KCH];
+    load_x_slice<KCH>(x, h, xr);
+    load_x_slice<KCH>(g, h, gr);
+    float ss = 0.f;
+#pragma unroll
+    for (int c = 0; c < KCH; ++c) {
+        ss = dot4(xr[c], xr[c], ss);
+        xr[c] = make_float4(xr[c].x * gr[c].x, xr[c].y * gr[c].y, xr[c].z * gr[c].z, xr[c].w * gr[c].w);
+    }
+    ss = block_sum(ss, red);
+    return 1.0f / sqrtf(ss / (float)h + eps);
+}
+
+// Output of a row-parallel stage: the shard's partial sum, or -- with the star reduce folded
+// in -- the reduced value: partials summed in rank order (this shard's own from the register,
+// the peers' from memory), then the shortcut.  Plain fp32 additions, nothing to contract.
+__device__ __forceinline__ void emit_row(const ShardView &s, const FusedReduce &rf, int row, float y)
+{
+    if (rf.n == 0) {
+        s.partial_out[row] = y;
+        return;
+    }
+    float acc = (rf.rank == 0) ? y : rf.peer[0][row];
+    for (int i = 1; i < rf.n; ++i) {
+        float v = (i == rf.rank) ? y : rf.peer[i][row];
+        acc = acc + v;
+    }
+    if (rf.residual) acc = acc + rf.residual[row];
+    rf.out[row] = acc;
+}
+
+// Stage 1: a unit is PAIRS rotary pairs (i, i + d/2) of one head, so a pair is
+// rotated in registers.  V rows use the same pairing, unrotated.
+template <int PAIRS, int KCH, int UB>
+__device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red)
+{
+    constexpr int ROWS = 2 * PAIRS;
+    const int half = a.d / 2;
+    const int npairs = (a.nq + 2 * a.nkv) * half;
+    const int n_units = (npairs + PAIRS - 1) / PAIRS;
+    auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
+#pragma unroll
+        for (int i = 0; i < PAIRS; ++i) {
+            int p = min(u * PAIRS + i, npairs - 1);
+            int hd = p / half, e = p - hd * half;
+            rows[2 * i] = s.w_qkv + ((size_t)hd * a.d + e) * a.h;
+            rows[2 * i + 1] = rows[2 * i] + (size_t)half * a.h;
+        }
+    };
+    RowStreamer<ROWS, KCH, UB> st;
+    st.prefetch(vwg, nvwg, n_units, a.h, rowfn);
+    if (vwg == 0 && threadIdx.x < a.nkv) s.ws_u32()[a.ws_cnt + threadIdx.x] = 0u;   // attention tickets
+    float4 xr[KCH];
+    const float rinv = norm_slice<KCH>(a.h_in, s.attn_norm, a.h, a.eps, xr, red);
+    auto epi = [&](int u, float (&y)[ROWS]) {
+#pragma unroll
+        for (int i = 0; i < PAIRS; ++i) {
+            int p = u * PAIRS + i;
+            if (threadIdx.x == i && p < npairs) {
+                int hd = p / half, e = p - hd * half;
+                float lo = y[2 * i] * rinv, hi = y[2 * i + 1] * rinv;
+                float *dst;
+                float cs = 1.f, sn = 0.f;
+                if (hd < a.nq + a.nkv && a.pos != 0) {
+                    // angle in fp64: it reaches pos radians, fp32 would lose the low bits of the phase
+                    double theta = exp2(-(2.0 * (double)e / (double)a.d) * a.log2_base);
+                    double sd, cd;
+                    sincos((double)a.pos * theta, &sd, &cd);
+                    cs = (float)cd;
+                    sn = (float)sd;
+                }
+                if (hd < a.nq) dst = s.ws + a.ws_q + (size_t)hd * a.d;
+                else if (hd < a.nq + a.nkv) dst = s.k + ((size_t)(hd - a.nq) * a.max_seq + a.pos) * a.d;
+                else dst = s.v + ((size_t)(hd - a.nq - a.nkv) * a.max_seq + a.pos) * a.d;
+                dst[e] = lo * cs - hi * sn;
+                dst[e + half] = hi * cs + lo * sn;
+            }
+        }
+    };
+    st.run(xr, red, rowfn, epi);
+}
+
+// Stage 3: a unit is ROWS rows of W_o; the input is the merged attention output.
+template <int ROWS, int KCH, int UB>
+__device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
+                                            const FusedReduce rf = FusedReduce{})
+{
+    const int dq = a.nq * a.d;
+    const int n_units = (a.h + ROWS - 1) / ROWS;
+    auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) rows[r] = s.w_o + (size_t)min(u * ROWS + r, a.h - 1) * dq;
+    };
+    RowStreamer<ROWS, KCH, UB> st;
+    st.prefetch(vwg, nvwg, n_units, dq, rowfn);
+    float4 xr[KCH];
+    load_x_slice<KCH>(s.ws + a.ws_o, dq, xr);
+    auto epi = [&](int u, float (&y)[ROWS]) {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            if (threadIdx.x == r && u * ROWS + r < a.h) emit_row(s, rf, u * ROWS + r, y[r]);
+    };
+    st.run(xr, red, rowfn, epi);
+}
+
+// Stage 4: a unit is COLS FFN columns j (rows gate_j and up_j), so
+// silu(gate_j) * up_j is formed in registers.
+template <int COLS, int KCH, int UB>
+__device__ __forceinline__ void stage_gate_up(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red)
+{
+    constexpr int ROWS = 2 * COLS;
+    const int n_units = (a.sl + COLS - 1) / COLS;
+    auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) {
+            size_t j = (size_t)min(u * COLS + c, a.sl - 1);
+            rows[2 * c] = s.w_gate + j * a.h;
+            rows[2 * c + 1] = s.w_up + j * a.h;
+        }
+    };
+    RowStreamer<ROWS, KCH, UB> st;
+    st.prefetch(vwg, nvwg, n_units, a.h, rowfn);
+    float4 xr[KCH];
+    const float rinv = norm_slice<KCH>(a.h_in, s.ffn_norm, a.h, a.eps, xr, red);
+    auto epi = [&](int u, float (&y)[ROWS]) {
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) {
+            int j = u * COLS + c;
+            if (threadIdx.x == c && j < a.sl) {
+                float gt = y[2 * c] * rinv, up = y[2 * c + 1] * rinv;
+                s.ws[a.ws_act + j] = gt / (1.0f + expf(-gt)) * up;
+            }
+        }
+    };
+    st.run(xr, red, rowfn, epi);
+}
+
+// Stage 5: a unit is ROWS rows of W_down.
+template <int ROWS, int KCH, int UB>
+__device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
+                                           const FusedReduce rf = FusedReduce{})
+{
+    const int n_units = (a.h + ROWS - 1) / ROWS;
+    auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) rows[r] = s.w_down + (size_t)min(u * ROWS + r, a.h - 1) * a.sl;
+    };
+    RowStreamer<ROWS, KCH, UB> st;
+    st.prefetch(vwg, nvwg, n_units, a.sl, rowfn);
+    float4 xr[KCH];
+    load_x_slice<KCH>(s.ws + a.ws_act, a.sl, xr);
+    auto epi = [&](int u, float (&y)[ROWS]) {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            if (threadIdx.x == r && u * ROWS + r < a.h) emit_row(s, rf, u * ROWS + r, y[r]);
+    };
+    st.run(xr, red, rowfn, epi);
+}
+
+// ---------------------------------------------------------------------------
+// Stage 2: attention of the local heads over cache slots 0..pos
+// ---------------------------------------------------------------------------
+// One workgroup = one KV head x one tile of GT of its query heads x one split
+// of the slots.  A tile is 64 slots, 16 per wave, and the four waves work
+// independently until the end:
+//   scores   a row of 16 lanes owns one slot (4 slots per pass, 4 passes);
+//            each lane holds EPL float4 of the key and of every query, the
+//            16 partial dot products meet in a DPP row reduction -- no LDS,
+//            no cross-lane memory traffic;
+//   softmax  wave-local running (max, sum) per head;
+//   values   a lane owns EPL consecutive elements of the head dimension, the
+//            wave's 16 V rows sit in registers, a slot's probability is
+//            broadcast with readlane.
+// The four wave partials meet in LDS; the split's (max, sum, unnormalised
+// output) goes to the workspace and the workgroup that takes the last ticket
+// of its KV head merges the splits into the normalised output.
+template <int EPL> struct VecOf;
+template <> struct VecOf<1> { typedef float T; };
+template <> struct VecOf<2> { typedef float2 T; };
+template <> struct VecOf<4> { typedef float4 T; };
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x)
+{
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+
+// sum over each row of 16 lanes, result in all 16 lanes
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp_mov<0xB1>(x);     // quad_perm [1,0,3,2]
+    x += dpp_mov<0x4E>(x);     // quad_perm [2,3,0,1]
+    x += dpp_mov<0x124>(x);    // row_ror 4
+    x += dpp_mov<0x128>(x);    // row_ror 8
+    return x;
+}
+
+// value of lane l (wave-uniform index) as a wave-uniform float
+__device__ __forceinline__ float lane_value(float x, int l)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+
+template <int GT, int EPL>
+__device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView &s, int split, int g, int ht,
+                                           float *smem)
+{
+    constexpr int TILE = 64, KPW = TILE / kWavesPerBlock, PASSES = KPW / 4;   // 16 slots per wave, 4 per pass
+    typedef typename VecOf<EPL>::T vec_t;
+    const int d = a.d;
+    float *wacc = smem;                            // [waves][GT][d]   wave partial outputs
+    float *wm = smem + kWavesPerBlock * GT * d;    // [waves][GT]      wave maxima
+    float *wl = wm + kWavesPerBlock * GT;          // [waves][GT]      wave sums
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int row = lane >> 4, eg = lane & 15;     // score phase: slot within the pass, slice of the head dimension
+    const int G = a.nq / a.nkv;
+    const int n_ht = (G + GT - 1) / GT;
+    const int n_valid = a.pos + 1;
+    const int t_begin = split * a.chunk_len;
+    const int t_end = min(t_begin + a.chunk_len, n_valid);
+    const float *Kg = s.k + (size_t)g * a.max_seq * d;
+    const float *Vg = s.v + (size_t)g * a.max_seq * d;
+    const float scale = 1.0f / sqrtf((float)d);
+    const int d4 = d / 4;
+    const bool e_ok = lane * EPL < d;              // value phase: this lane's elements exist
+    TPI_TRACE_AT(split, 0);
+
+    // this lane's slice of every query of the tile (rotated q, scaled once here)
+    float4 qv[GT][EPL];
+#pragma unroll
+    for (int j = 0; j < GT; ++j) {
+        int hj = min(ht * GT + j, G - 1);
+        const float *qp = s.ws + a.ws_q + (size_t)(g * G + hj) * d;
+#pragma unroll
+        for (int c = 0; c < EPL; ++c) {
+            int e = (eg * EPL + c) * 4;
+            float4 v = (e < d) ? *reinterpret_cast<const float4 *>(qp + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+            qv[j][c] = make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
+        }
+    }
+    float m_run[GT], l_run[GT];
+    vec_t acc[GT];
+#pragma unroll
+    for (int j = 0; j < GT; ++j) {
+        m_run[j] = -INFINITY; l_run[j] = 0.f;
+        float *ap = reinterpret_cast<float *>(&acc[j]);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) ap[i] = 0.f;
+    }
+
+    for (int t0 = t_begin; t0 < t_end; t0 += TILE) {
+        const int tw = t0 + wave * KPW;            // first slot of this wave in the tile
+        float4 kr[PASSES][EPL];
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            int t = tw + i * 4 + row;
+#pragma unroll
+            for (int c = 0; c < EPL; ++c) {
+                int e = (eg * EPL + c) * 4;
+                kr[i][c] = (t < t_end && e < d) ? *reinterpret_cast<const float4 *>(Kg + (size_t)t * d + e)
+                                                : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        vec_t vr[KPW];
+#pragma unroll
+        for (int k = 0; k < KPW; ++k) {
+            float *vp = reinterpret_cast<float *>(&vr[k]);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) vp[i] = 0.f;
+            if (e_ok && tw + k < t_end) vr[k] = *reinterpret_cast<const vec_t *>(Vg + (size_t)(tw + k) * d + lane * EPL);
+        }
+        TPI_TRACE_AT(split, 1);
+        // scores of slot (pass i, row) against every head, in all 16 lanes of the row
+        float sc[PASSES][GT];
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            const bool ok = tw + i * 4 + row < t_end;
+#pragma unroll
+            for (int j = 0; j < GT; ++j) {
+                float p = 0.f;
+#pragma unroll
+                for (int c = 0; c < EPL; ++c) p = dot4(qv[j][c], kr[i][c], p);
+                p = row16_sum(p);
+                sc[i][j] = ok ? p : -INFINITY;
+            }
+        }
+        TPI_TRACE_AT(split, 2);
+        // wave-local running softmax: maximum and sum over the wave's 16 slots
+#pragma unroll
+        for (int j = 0; j < GT; ++j) {
+            float mt = sc[0][j];
+#pragma unroll
+            for (int i = 1; i < PASSES; ++i) mt = fmaxf(mt, sc[i][j]);
+            mt = fmaxf(fmaxf(lane_value(mt, 0), lane_value(mt, 16)), fmaxf(lane_value(mt, 32), lane_value(mt, 48)));
+            const float m_new = fmaxf(m_run[j], mt);
+            float ls = 0.f;
+#pragma unroll
+            for (int i = 0; i < PASSES; ++i) {
+                sc[i][j] = (sc[i][j] == -INFINITY) ? 0.f : __expf(sc[i][j] - m_new);
+                ls += sc[i][j];
+            }
+            ls = (lane_value(ls, 0) + lane_value(ls, 16)) + (lane_value(ls, 32) + lane_value(ls, 48));
+            const float al = (m_run[j] == -INFINITY) ? 0.f : __expf(m_run[j] - m_new);
+            l_run[j] = l_run[j] * al + ls;
+            m_run[j] = m_new;
+            float *ap = reinterpret_cast<float *>(&acc[j]);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) ap[i] *= al;
+        }
+        TPI_TRACE_AT(split, 3);
+        // values: slot k of the wave = (pass k / 4, row k % 4); its probability sits in lane 16 * row
+#pragma unroll
+        for (int k = 0; k < KPW; ++k) {
+            const float *vp = reinterpret_cast<const float *>(&vr[k]);
+#pragma unroll
+            for (int j = 0; j < GT; ++j) {
+                float pk = lane_value(sc[k / 4][j], 16 * (k % 4));
+                float *ap = reinterpret_cast<float *>(&acc[j]);
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) ap[i] = fmaf(pk, vp[i], ap[i]);
+            }
+        }
+    }
+    TPI_TRACE_AT(split, 4);
+
+    // the four waves' partials meet in LDS
+#pragma unroll
+    for (int j = 0; j < GT; ++j) {
+        if (e_ok) *reinterpret_cast<vec_t *>(wacc + (size_t)(wave * GT + j) * d + lane * EPL) = acc[j];
+        if (lane == 0) { wm[wave * GT + j] = m_run[j]; wl[wave * GT + j] = l_run[j]; }
+    }
+    __syncthreads();
+    const int total = a.n_splits * n_ht;           // workgroups per KV head
+    for (int i = tid; i < GT * d4; i += kBlock) {
+        int j = i / d4, c = i - j * d4;
+        if (ht * GT + j >= G) continue;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) M = fmaxf(M, wm[w * GT + j]);
+        float L = 0.f;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            float mw = wm[w * GT + j];
+            float wt = (mw == -INFINITY) ? 0.f : __expf(mw - M);
+            L = fmaf(wt, wl[w * GT + j], L);
+            float4 v = *reinterpret_cast<const float4 *>(wacc + (size_t)(w * GT + j) * d + c * 4);
+            o.x = fmaf(wt, v.x, o.x); o.y = fmaf(wt, v.y, o.y);
+            o.z = fmaf(wt, v.z, o.z); o.w = fmaf(wt, v.w, o.w);
+        }
+        const int head = g * G + ht * GT + j;
+        if (total == 1) {
+            float inv = 1.0f / L;
+            *reinterpret_cast<float4 *>(s.ws + a.ws_o + (size_t)head * d + c * 4) =
+                make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+        } else {
+            *reinterpret_cast<float4 *>(s.ws + a.ws_att_acc + ((size_t)head * kAttnMaxSplits + split) * d + c * 4) = o;
+            if (c == 0) {
+                s.ws[a.ws_att_m + head * kAttnMaxSplits + split] = M;
+                s.ws[a.ws_att_l + head * kAttnMaxSplits + split] = L;
+            }
+        }
+    }
+    if (total == 1) return;
+
+    // the last workgroup of this KV head to arrive merges the splits.  One thread carries the
+    // release / acquire fences for the workgroup: the barrier before it has drained every wave's
+    // stores to L2, and the barrier after it orders every wave's loads behind the invalidate.
+    TPI_TRACE_AT(split, 5);
+    __syncthreads();
+    if (tid == 0) {
+        __threadfence();
+        unsigned old = atomicAdd(s.ws_u32() + a.ws_cnt + g, 1u);
+        s_last = (old == (unsigned)total - 1u);
+        if (s_last) __threadfence();
+    }
+    __syncthreads();
+    TPI_TRACE_AT(split, 7);
+    if (!s_last) return;
+    TPI_TRACE_AT(split, 8);
+    for (int i = tid; i < G * d4; i += kBlock) {
+        int j = i / d4, c = i - j * d4;
+        int head = g * G + j;
+        const float *mp = s.ws + a.ws_att_m + head * kAttnMaxSplits;
+        const float *lp = s.ws + a.ws_att_l + head * kAttnMaxSplits;
+        const float *ap = s.ws + a.ws_att_acc + (size_t)head * kAttnMaxSplits * d + c * 4;
+        // all loads of a batch are issued before any is used: the partials come from other
+        // compute units' writes, every one of them a trip to memory
+        float wgt[kAttnMaxSplits], lv[kAttnMaxSplits];
+        float M = -INFINITY;
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
+            wgt[sp] = (sp < a.n_splits) ? mp[sp] : -INFINITY;
+            lv[sp] = (sp < a.n_splits) ? lp[sp] : 0.f;
+        }
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) M = fmaxf(M, wgt[sp]);
+        float L = 0.f;
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
+            wgt[sp] = (sp < a.n_splits) ? __expf(wgt[sp] - M) : 0.f;
+            L = fmaf(wgt[sp], lv[sp], L);
+        }
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int sp0 = 0; sp0 < kAttnMaxSplits; sp0 += 8) {
+            if (sp0 < a.n_splits) {
+                float4 v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    v[i] = (sp0 + i < a.n_splits) ? *reinterpret_cast<const float4 *>(ap + (size_t)(sp0 + i) * d)
+                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    float w = wgt[sp0 + i];
+                    o.x = fmaf(w, v[i].x, o.x); o.y = fmaf(w, v[i].y, o.y);
+                    o.z = fmaf(w, v[i].z, o.z); o.w = fmaf(w, v[i].w, o.w);
+                }
+            }
+        }
+        float inv = 1.0f / L;
+        *reinterpret_cast<float4 *>(s.ws + a.ws_o + (size_t)head * d + c * 4) =
+            make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+    }
+    TPI_TRACE_AT(split, 9);
+    if (tid == 0) s.ws_u32()[a.ws_cnt + g] = 0u;  // ready for the next call
+}
+
+}  // namespace tpi

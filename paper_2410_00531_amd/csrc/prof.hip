@@ -67,3 +67,4 @@ int tpi_prof_read(double *total_ms, int32_t *launches)
 }
 
 }  // extern "C"
+

@@ -7,7 +7,7 @@
 namespace tpi {
 
 enum Stage { kStageNone = 0, kStageQkv = 1, kStageAttn = 2, kStageOproj = 3, kStageGateUp = 4, kStageDown = 5,
-             kStageReduce = 6, kStagePrefillGemm = 7, kStageCount };
+             kStageReduce = 6, kStagePrefillGemm = 7, kStageToken = 8, kStageCount };
 
 void prof_begin(int stage, hipStream_t st);
 void prof_end(int stage, hipStream_t st);

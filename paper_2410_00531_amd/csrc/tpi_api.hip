@@ -55,18 +55,20 @@ int check_cfg(const tpi_shard_cfg *c)
 }
 
 // Workspace layout of a decode call (offsets in floats).
-static void decode_layout(const tpi_shard_cfg *c, DecodeArgs &a)
+static void decode_layout(const tpi_shard_cfg *c, DecodeDims &a)
 {
     int off = 0;
     a.ws_q = off;        off += round4(c->n_q_local * c->head_dim);
     a.ws_att_m = off;    off += round4(c->n_q_local * kAttnMaxSplits);
     a.ws_att_l = off;    off += round4(c->n_q_local * kAttnMaxSplits);
     a.ws_att_acc = off;  off += round4(c->n_q_local * kAttnMaxSplits * c->head_dim);
+    a.ws_o = off;        off += round4(c->n_q_local * c->head_dim);
     a.ws_act = off;      off += round4(c->ffn_local);
+    a.ws_cnt = off;      off += round4(c->n_kv_local);
     a.ws_total = off;
 }
 
-static int fill_decode_args(const tpi_shard_cfg *c, int32_t pos, const float *h_in, DecodeArgs &a)
+int fill_decode_dims(const tpi_shard_cfg *c, int32_t pos, const float *h_in, DecodeDims &a)
 {
     a.h = c->hidden; a.nq = c->n_q_local; a.nkv = c->n_kv_local; a.d = c->head_dim; a.sl = c->ffn_local;
     a.max_seq = c->max_seq; a.pos = pos; a.eps = c->rms_eps;
@@ -106,7 +108,7 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
 
     DecodeArgs a;
     std::memset(&a, 0, sizeof(a));
-    fill_decode_args(cfg, pos, h_in, a);
+    fill_decode_dims(cfg, pos, h_in, a);
     for (int r = 0; r < n_shards; ++r) {
         const tpi_layer_weights &lw = w[r];
         ShardView &s = a.s[r];

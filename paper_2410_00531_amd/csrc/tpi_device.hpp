@@ -5,9 +5,22 @@
 
 namespace tpi {
 
+// Development aid, compiled in only with -DTPI_TRACE: thread 0 of a workgroup
+// stamps the 100 MHz wall clock into a global table (slot-major per workgroup).
+#ifdef TPI_TRACE
+__device__ unsigned long long g_trace[1 << 16];   // one definition: include from one source file only
+#define TPI_TRACE_AT(wg, slot)                                                              \
+    do {                                                                                    \
+        if (threadIdx.x == 0 && (wg) < 2048) g_trace[(wg) * 16 + (slot)] = wall_clock64();  \
+    } while (0)
+#else
+#define TPI_TRACE_AT(wg, slot) do { } while (0)
+#endif
+
 constexpr int kWave = 64;
 constexpr int kBlock = 256;              // threads per workgroup of every streaming kernel
 constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kChunk = kBlock * 4;       // floats one workgroup covers with one float4 per thread
 
 __device__ __forceinline__ float wave_sum(float v)
 {
@@ -55,69 +68,125 @@ __device__ __forceinline__ float block_sum(float v, float *red)
     return s;
 }
 
-// y[r] = sum_k rows[r][k] * xs[k] for ROWS rows of length K (K % 4 == 0, rows
-// 16-byte aligned), the 256 threads of the workgroup striding over k.  xs is
-// in LDS.  pre holds the loads of the first batch, issued by the caller
-// before xs was ready (weights do not depend on activations).  On return
-// every thread holds all ROWS sums.  red: ROWS * kWavesPerBlock floats of LDS.
-template <int ROWS, int U>
-struct GemvTile {
-    float4 w[U][ROWS];
-
-    __device__ __forceinline__ void issue(const float *const (&rows)[ROWS], int K, int k0)
-    {
+// The slice of an input vector that one thread multiplies with: element group
+// (c * 256 + tid) of every 1024-float chunk c.  The same slice meets every
+// weight row, so it stays in registers for the whole stage (no LDS staging).
+template <int KCH>
+__device__ __forceinline__ void load_x_slice(const float *x, int K, float4 (&xr)[KCH])
+{
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int k = k0 + (u * kBlock + threadIdx.x) * 4;
+    for (int c = 0; c < KCH; ++c) {
+        int k = c * kChunk + threadIdx.x * 4;
+        xr[c] = (k < K) ? *reinterpret_cast<const float4 *>(x + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+// Streams the weight rows of a sequence of units through registers, two
+// batches deep: while batch s is multiplied, batch s+1 (possibly the next
+// unit's first) is already in flight, so the memory pipe does not drain at a
+// unit's reduction.  A unit is ROWS rows of length K (K % 4 == 0, rows
+// 16-byte aligned); a batch is UB chunks of 1024 floats of each row.
+//
+//   RowFn(unit, const float *(&rows)[ROWS])  sets the unit's row pointers
+//   EpiFn(unit, float (&y)[ROWS])            consumes the unit's ROWS sums
+//                                            (every thread holds all of them)
+// Units first, first + stride, ... < n_units are processed.  prefetch() may be
+// called before the input slice exists; run() needs it.  red: ROWS * 4 floats.
+template <int ROWS, int KCH, int UB>
+struct RowStreamer {
+    static constexpr int NB = (KCH + UB - 1) / UB;   // batches per unit
+    float4 wa[UB][ROWS], wb[UB][ROWS];
+    int unit, stride, n_units, K;
+
+    template <class RowFn>
+    __device__ __forceinline__ void issue(float4 (&w)[UB][ROWS], int u, int b, RowFn &rowfn)
+    {
+        const float *rows[ROWS];
+        rowfn(u, rows);
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+            int k = (b * UB + i) * kChunk + threadIdx.x * 4;
 #pragma unroll
             for (int r = 0; r < ROWS; ++r)
-                w[u][r] = (k < K) ? load_stream4(rows[r] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+                w[i][r] = (k < K) ? load_stream4(rows[r] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
 
-    __device__ __forceinline__ void consume(const float *xs, int K, int k0, float (&acc)[ROWS])
+    __device__ __forceinline__ void consume(const float4 (&w)[UB][ROWS], int b, const float4 (&xr)[KCH],
+                                            float (&acc)[ROWS])
     {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int k = k0 + (u * kBlock + threadIdx.x) * 4;
-            if (k < K) {
-                float4 x = *reinterpret_cast<const float4 *>(xs + k);
+        for (int i = 0; i < UB; ++i) {
+            // b is a run-time value: pick the slice with a compile-time index per batch
 #pragma unroll
-                for (int r = 0; r < ROWS; ++r) acc[r] = dot4(w[u][r], x, acc[r]);
+            for (int bb = 0; bb < NB; ++bb) {
+                if (bb == b && bb * UB + i < KCH) {
+#pragma unroll
+                    for (int r = 0; r < ROWS; ++r) acc[r] = dot4(w[i][r], xr[bb * UB + i], acc[r]);
+                }
             }
         }
     }
-};
 
-template <int ROWS, int U>
-__device__ __forceinline__ void gemv_rows(const float *const (&rows)[ROWS], int K, const float *xs,
-                                          GemvTile<ROWS, U> &tile, float *red, float (&y)[ROWS])
-{
-    constexpr int kStep = U * kBlock * 4;
-    float acc[ROWS];
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) acc[r] = 0.f;
-    for (int k0 = 0;;) {
-        tile.consume(xs, K, k0, acc);
-        k0 += kStep;
-        if (k0 >= K) break;
-        tile.issue(rows, K, k0);
+    template <class RowFn>
+    __device__ __forceinline__ void prefetch(int first, int stride_, int n_units_, int K_, RowFn &rowfn)
+    {
+        unit = first; stride = stride_; n_units = n_units_; K = K_;
+        if (unit < n_units) issue(wa, unit, 0, rowfn);
     }
+
+    template <class EpiFn>
+    __device__ __forceinline__ void finish_unit(int u, float (&acc)[ROWS], float *red, EpiFn &epi)
+    {
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) acc[r] = wave_sum(acc[r]);
-    if ((threadIdx.x & (kWave - 1)) == 0) {
+        for (int r = 0; r < ROWS; ++r) acc[r] = wave_sum(acc[r]);
+        if ((threadIdx.x & (kWave - 1)) == 0) {
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) red[r * kWavesPerBlock + threadIdx.x / kWave] = acc[r];
+            for (int r = 0; r < ROWS; ++r) red[r * kWavesPerBlock + threadIdx.x / kWave] = acc[r];
+        }
+        __syncthreads();
+        float y[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWavesPerBlock; ++w) s += red[r * kWavesPerBlock + w];
+            y[r] = s;
+            acc[r] = 0.f;
+        }
+        __syncthreads();
+        epi(u, y);
     }
-    __syncthreads();
+
+    template <class RowFn, class EpiFn>
+    __device__ __forceinline__ void run(const float4 (&xr)[KCH], float *red, RowFn &rowfn, EpiFn &epi)
+    {
+        float acc[ROWS];
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        float s = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWavesPerBlock; ++w) s += red[r * kWavesPerBlock + w];
-        y[r] = s;
+        for (int r = 0; r < ROWS; ++r) acc[r] = 0.f;
+        int u = unit, b = 0;
+        if (u >= n_units) return;
+        while (true) {
+            // current step sits in wa
+            int nu = u, nb = b + 1;
+            if (nb == NB) { nb = 0; nu = u + stride; }
+            bool more = nu < n_units;
+            if (more) issue(wb, nu, nb, rowfn);
+            consume(wa, b, xr, acc);
+            if (b == NB - 1) finish_unit(u, acc, red, epi);
+            if (!more) break;
+            u = nu; b = nb;
+            // current step sits in wb
+            nu = u; nb = b + 1;
+            if (nb == NB) { nb = 0; nu = u + stride; }
+            more = nu < n_units;
+            if (more) issue(wa, nu, nb, rowfn);
+            consume(wb, b, xr, acc);
+            if (b == NB - 1) finish_unit(u, acc, red, epi);
+            if (!more) break;
+            u = nu; b = nb;
+        }
     }
-    __syncthreads();
-}
+};
 
 }  // namespace tpi

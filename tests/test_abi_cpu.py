@@ -47,8 +47,8 @@ def _code(fn, *a, **k):
 def test_workspace_bytes():
     cfg = B.make_cfg(8192, 8, 1, 128, 3584, 1100)
     n = B.tpi_workspace_bytes(cfg, 1)
-    # q + split maxima and sums + split outputs + activation, in floats
-    assert n == 4 * (1024 + 2 * 8 * 32 + 8 * 32 * 128 + 3584)
+    # q + split maxima and sums + split outputs + merged output + activation + tickets, in floats
+    assert n == 4 * (1024 + 2 * 8 * 32 + 8 * 32 * 128 + 1024 + 3584 + 4)
     assert B.tpi_workspace_bytes(B.make_cfg(8192, 8, 3, 128, 3584, 1100), 1) == 0
     assert B.tpi_workspace_bytes(cfg, 0) == 0
 
