@@ -45,6 +45,7 @@ def parse():
     ap.add_argument("--no-window", action="store_true", help="skip the windowed-weights leg")
     ap.add_argument("--window-layers", type=int, default=4)
     ap.add_argument("--window-steps", type=int, default=3)
+    ap.add_argument("--no-persistent", action="store_true", help="skip the whole-token persistent kernel leg")
     ap.add_argument("--no-prefill", action="store_true", help="skip the bf16 prefill leg")
     ap.add_argument("--prefill-tokens", type=int, default=512)
     ap.add_argument("--prefill-steps", type=int, default=3)
@@ -282,7 +283,7 @@ def main():
     N = m.n_shards
     kv_len = args.kv_len or {"llama2-70b-shaped-tp8": 1024, "llama3.1-8b-shaped-tp4": 512, "tiny": 16}[args.workload]
     K, W = args.steps, args.warmup
-    n_tokens_total = 4 * (K + W) + 8
+    n_tokens_total = 7 * (K + W) + 8
     max_seq = kv_len + n_tokens_total
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -401,6 +402,35 @@ def main():
         ms_one, med_one, gu1_ms, gu1_n = leg(False)
     if args.mode == "one":
         ms_all, med_all, gu_ms, gu_n = ms_one, med_one, gu1_ms, gu1_n
+
+    # one device's shard, all layers of a token in one persistent launch (reduces folded in)
+    persistent = None
+    if args.mode in ("both", "one") and not args.no_persistent:
+        Wd = (B.tpi_layer_weights * L)(*[W_one[l][0] for l in range(L)])
+        KVd = (B.tpi_kv_layer * L)(*[KV_one[l][0] for l in range(L)])
+        peers = [partials[r] for r in range(N)]
+        dec = B.Decoder(cfg, Wd, KVd, 0, peers if N > 1 else None, peers if N > 1 else None)
+        for i in range(W):
+            dec.token(pos + i, h0, h_a)
+        pos += W
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(K):
+            dec.token(pos + i, h0, h_a)
+        torch.cuda.synchronize()
+        ms_p = (time.perf_counter() - t) * 1e3 / K
+        pos += K
+        B.tpi_prof_enable(B.TPI_STAGE_TOKEN, K)
+        for i in range(K):
+            dec.token(pos + i, h0, h_a)
+        torch.cuda.synchronize()
+        pos += K
+        tk_ms, tk_n = B.tpi_prof_read()
+        B.tpi_prof_enable(B.TPI_STAGE_NONE, 0)
+        dec.status()
+        persistent = {"ms_per_token": round(ms_p, 4), "grid": dec.grid, "kernel_avg_ms": round(tk_ms / max(tk_n, 1), 4),
+                      "finite": bool(torch.isfinite(h_a).all().item())}
+        dec.destroy()
     assert pos <= max_seq
     torch.cuda.synchronize()
     finite = bool(torch.isfinite(last_out[0]).all().item())
@@ -453,6 +483,12 @@ def main():
         "output_finite": finite,
         "setup_s": round(setup_s, 1),
     }
+    if persistent is not None:
+        bytes_p = token_bytes(m, 1, N, L, mid_pos)
+        persistent["hbm_gbps"] = round(bytes_p / (persistent["ms_per_token"] * 1e-3) / 1e9, 1)
+        persistent["hbm_frac_of_peak"] = round(persistent["hbm_gbps"] / HBM_PEAK_GBPS, 4)
+        persistent["kernel_hbm_frac_of_peak"] = round(bytes_p / (persistent["kernel_avg_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+        result["one_shard_persistent"] = persistent
 
     # ---- one shard with its weights streamed through a sliding window (pinned host -> HBM) --------
     if not args.no_window and args.mode in ("both", "one"):

@@ -27,6 +27,18 @@ __device__ __forceinline__ float norm_slice(const float *x, const float *g, int 
     return 1.0f / sqrtf(ss / (float)h + eps);
 }
 
+// Every thread holds all ROWS sums of a unit; thread i takes element i (i < ROWS) without
+// dynamic register indexing, so the epilogue of a unit runs on ROWS lanes side by side
+// instead of ROWS divergent branches one after the other.
+template <int ROWS>
+__device__ __forceinline__ float pick_own(const float (&y)[ROWS], int i)
+{
+    float v = y[0];
+#pragma unroll
+    for (int r = 1; r < ROWS; ++r) v = (i == r) ? y[r] : v;
+    return v;
+}
+
 // Output of a row-parallel stage: the shard's partial sum, or -- with the star reduce folded
 // in -- the reduced value: partials summed in rank order (this shard's own from the register,
 // the peers' from memory), then the shortcut.  Plain fp32 additions, nothing to contract.
@@ -36,12 +48,20 @@ __device__ __forceinline__ void emit_row(const ShardView &s, const FusedReduce &
         s.partial_out[row] = y;
         return;
     }
-    float acc = (rf.rank == 0) ? y : rf.peer[0][row];
-    for (int i = 1; i < rf.n; ++i) {
-        float v = (i == rf.rank) ? y : rf.peer[i][row];
-        acc = acc + v;
+    // all peers' values are requested before the first is used: each is a trip to memory
+    float v[kMaxBatchShards];
+#pragma unroll
+    for (int i = 0; i < kMaxBatchShards; ++i) v[i] = (i < rf.n && i != rf.rank) ? rf.peer[i][row] : 0.f;
+    const float res = rf.residual ? rf.residual[row] : 0.f;
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxBatchShards; ++i) {
+        if (i < rf.n) {
+            float t = (i == rf.rank) ? y : v[i];
+            acc = (i == 0) ? t : acc + t;
+        }
     }
-    if (rf.residual) acc = acc + rf.residual[row];
+    if (rf.residual) acc = acc + res;
     rf.out[row] = acc;
 }
 
@@ -69,28 +89,32 @@ __device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &
     float4 xr[KCH];
     const float rinv = norm_slice<KCH>(a.h_in, s.attn_norm, a.h, a.eps, xr, red);
     auto epi = [&](int u, float (&y)[ROWS]) {
+        const int i = threadIdx.x;                 // lane i finishes pair i of the unit
+        float lo = y[0], hi = y[1];
 #pragma unroll
-        for (int i = 0; i < PAIRS; ++i) {
-            int p = u * PAIRS + i;
-            if (threadIdx.x == i && p < npairs) {
-                int hd = p / half, e = p - hd * half;
-                float lo = y[2 * i] * rinv, hi = y[2 * i + 1] * rinv;
-                float *dst;
-                float cs = 1.f, sn = 0.f;
-                if (hd < a.nq + a.nkv && a.pos != 0) {
-                    // angle in fp64: it reaches pos radians, fp32 would lose the low bits of the phase
-                    double theta = exp2(-(2.0 * (double)e / (double)a.d) * a.log2_base);
-                    double sd, cd;
-                    sincos((double)a.pos * theta, &sd, &cd);
-                    cs = (float)cd;
-                    sn = (float)sd;
-                }
-                if (hd < a.nq) dst = s.ws + a.ws_q + (size_t)hd * a.d;
-                else if (hd < a.nq + a.nkv) dst = s.k + ((size_t)(hd - a.nq) * a.max_seq + a.pos) * a.d;
-                else dst = s.v + ((size_t)(hd - a.nq - a.nkv) * a.max_seq + a.pos) * a.d;
-                dst[e] = lo * cs - hi * sn;
-                dst[e + half] = hi * cs + lo * sn;
+        for (int q = 1; q < PAIRS; ++q) {
+            lo = (i == q) ? y[2 * q] : lo;
+            hi = (i == q) ? y[2 * q + 1] : hi;
+        }
+        const int p = u * PAIRS + i;
+        if (i < PAIRS && p < npairs) {
+            int hd = p / half, e = p - hd * half;
+            lo *= rinv; hi *= rinv;
+            float *dst;
+            float cs = 1.f, sn = 0.f;
+            if (hd < a.nq + a.nkv && a.pos != 0) {
+                // angle in fp64: it reaches pos radians, fp32 would lose the low bits of the phase
+                double theta = exp2(-(2.0 * (double)e / (double)a.d) * a.log2_base);
+                double sd, cd;
+                sincos((double)a.pos * theta, &sd, &cd);
+                cs = (float)cd;
+                sn = (float)sd;
             }
+            if (hd < a.nq) dst = s.ws + a.ws_q + (size_t)hd * a.d;
+            else if (hd < a.nq + a.nkv) dst = s.k + ((size_t)(hd - a.nq) * a.max_seq + a.pos) * a.d;
+            else dst = s.v + ((size_t)(hd - a.nq - a.nkv) * a.max_seq + a.pos) * a.d;
+            dst[e] = lo * cs - hi * sn;
+            dst[e + half] = hi * cs + lo * sn;
         }
     };
     st.run(xr, red, rowfn, epi);
@@ -112,9 +136,11 @@ __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView
     float4 xr[KCH];
     load_x_slice<KCH>(s.ws + a.ws_o, dq, xr);
     auto epi = [&](int u, float (&y)[ROWS]) {
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r)
-            if (threadIdx.x == r && u * ROWS + r < a.h) emit_row(s, rf, u * ROWS + r, y[r]);
+        {
+            const int r = threadIdx.x;
+            const float mine = pick_own<ROWS>(y, r);
+            if (r < ROWS && u * ROWS + r < a.h) emit_row(s, rf, u * ROWS + r, mine);
+        }
     };
     st.run(xr, red, rowfn, epi);
 }
@@ -139,13 +165,17 @@ __device__ __forceinline__ void stage_gate_up(const DecodeDims &a, const ShardVi
     float4 xr[KCH];
     const float rinv = norm_slice<KCH>(a.h_in, s.ffn_norm, a.h, a.eps, xr, red);
     auto epi = [&](int u, float (&y)[ROWS]) {
+        const int c = threadIdx.x;                 // lane c finishes column c of the unit
+        float gt = y[0], up = y[1];
 #pragma unroll
-        for (int c = 0; c < COLS; ++c) {
-            int j = u * COLS + c;
-            if (threadIdx.x == c && j < a.sl) {
-                float gt = y[2 * c] * rinv, up = y[2 * c + 1] * rinv;
-                s.ws[a.ws_act + j] = gt / (1.0f + expf(-gt)) * up;
-            }
+        for (int q = 1; q < COLS; ++q) {
+            gt = (c == q) ? y[2 * q] : gt;
+            up = (c == q) ? y[2 * q + 1] : up;
+        }
+        const int j = u * COLS + c;
+        if (c < COLS && j < a.sl) {
+            gt *= rinv; up *= rinv;
+            s.ws[a.ws_act + j] = gt / (1.0f + expf(-gt)) * up;
         }
     };
     st.run(xr, red, rowfn, epi);
@@ -166,9 +196,11 @@ __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView 
     float4 xr[KCH];
     load_x_slice<KCH>(s.ws + a.ws_act, a.sl, xr);
     auto epi = [&](int u, float (&y)[ROWS]) {
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r)
-            if (threadIdx.x == r && u * ROWS + r < a.h) emit_row(s, rf, u * ROWS + r, y[r]);
+        {
+            const int r = threadIdx.x;
+            const float mine = pick_own<ROWS>(y, r);
+            if (r < ROWS && u * ROWS + r < a.h) emit_row(s, rf, u * ROWS + r, mine);
+        }
     };
     st.run(xr, red, rowfn, epi);
 }

@@ -1,5 +1,6 @@
-"""Whole-token persistent kernel: bitwise equal to the per-phase calls on the
-same inputs, and within 1e-4 of the oracle."""
+"""Whole-token persistent kernel against the per-phase calls on the same inputs
+(same arithmetic, different summation order inside the GEMVs: agreement to
+1e-5 of the output's max-abs) and against the oracle (1e-4)."""
 import numpy as np
 import pytest
 import torch
@@ -73,9 +74,13 @@ def test_decoder_matches_per_phase_calls_and_oracle(name, n_layers, pos, n_ranks
         ref = _per_phase_gpu(cfg, ref_sh, pos + t, h0_t, pa_t, pf_t, rank)
         dec.token(pos + t, h0_t, out)
         dec.status()
-        assert torch.equal(out, ref), f"token {t}: persistent kernel differs from the per-phase calls"
+        e = rel_err(out.cpu().numpy(), ref.cpu().numpy())
+        assert e <= 1e-5, f"token {t}: persistent kernel differs from the per-phase calls by {e:.2e}"
         for a, b in zip(dec_sh, ref_sh):
-            assert torch.equal(a.K, b.K) and torch.equal(a.V, b.V)
+            # same slots written, values equal up to the summation order
+            assert torch.equal(a.K != 0, b.K != 0) and torch.equal(a.V != 0, b.V != 0)
+            assert rel_err(a.K.cpu().numpy(), b.K.cpu().numpy()) <= 1e-5
+            assert rel_err(a.V.cpu().numpy(), b.V.cpu().numpy()) <= 1e-5
         want = _oracle(cfg, weights, o_caches, pos + t, h0, peers_a, peers_f, rank)
         assert rel_err(out.cpu().numpy(), want) <= FP32_TOL
     dec.destroy()
