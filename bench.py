@@ -45,7 +45,9 @@ def parse():
     ap.add_argument("--no-window", action="store_true", help="skip the windowed-weights leg")
     ap.add_argument("--window-layers", type=int, default=4)
     ap.add_argument("--window-steps", type=int, default=3)
-    ap.add_argument("--no-persistent", action="store_true", help="skip the whole-token persistent kernel leg")
+    ap.add_argument("--no-fused", action="store_true", help="skip the reduce-folded-into-phase leg")
+    ap.add_argument("--persistent", dest="no_persistent", action="store_false", default=True,
+                    help="also time the whole-token persistent kernel (switched off in the library for now)")
     ap.add_argument("--no-prefill", action="store_true", help="skip the bf16 prefill leg")
     ap.add_argument("--prefill-tokens", type=int, default=512)
     ap.add_argument("--prefill-steps", type=int, default=3)
@@ -283,7 +285,7 @@ def main():
     N = m.n_shards
     kv_len = args.kv_len or {"llama2-70b-shaped-tp8": 1024, "llama3.1-8b-shaped-tp4": 512, "tiny": 16}[args.workload]
     K, W = args.steps, args.warmup
-    n_tokens_total = 7 * (K + W) + 8
+    n_tokens_total = 9 * (K + W) + 8
     max_seq = kv_len + n_tokens_total
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -341,18 +343,38 @@ def main():
 
     last_out = [h0]
 
-    def token(pos, all_shards=True):
-        """One token through the stack; returns the output hidden state tensor."""
-        Wl, KVl, Pl, WSl, n = (W_all, KV_all, P_all, WS_all, N) if all_shards else (W_one, KV_one, P_one, WS_one, 1)
+    def token(pos, all_shards=True, fused=False):
+        """One token through the stack; returns the output hidden state tensor.  All shards: batched
+        phase launches + star reduce kernels.  One shard: one device's view; the 8-way reduce runs over
+        its own partial and the 7 peers' partial buffers, either as the separate star-reduce launch or
+        (fused) folded into the phase's last stage."""
         src, dst = h0, h_a
-        for l in range(L):
-            check(lib.tpi_shards_layer_decode(cfg_p, n, Wl[l], KVl[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
-                                              Pl, WSl, stream))
-            check(lib.tpi_star_reduce(P_all, N, m.hidden, src.data_ptr(), h_attn.data_ptr(), stream))
-            check(lib.tpi_shards_layer_decode(cfg_p, n, Wl[l], None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
-                                              Pl, WSl, stream))
-            check(lib.tpi_star_reduce(P_all, N, m.hidden, h_attn.data_ptr(), dst.data_ptr(), stream))
-            src, dst = dst, (h_b if dst is h_a else h_a)
+        if all_shards:
+            for l in range(L):
+                check(lib.tpi_shards_layer_decode(cfg_p, N, W_all[l], KV_all[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
+                                                  P_all, WS_all, stream))
+                check(lib.tpi_star_reduce(P_all, N, m.hidden, src.data_ptr(), h_attn.data_ptr(), stream))
+                check(lib.tpi_shards_layer_decode(cfg_p, N, W_all[l], None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
+                                                  P_all, WS_all, stream))
+                check(lib.tpi_star_reduce(P_all, N, m.hidden, h_attn.data_ptr(), dst.data_ptr(), stream))
+                src, dst = dst, (h_b if dst is h_a else h_a)
+        elif not fused:
+            for l in range(L):
+                check(lib.tpi_shards_layer_decode(cfg_p, 1, W_one[l], KV_one[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
+                                                  P_one, WS_one, stream))
+                check(lib.tpi_star_reduce(P_all, N, m.hidden, src.data_ptr(), h_attn.data_ptr(), stream))
+                check(lib.tpi_shards_layer_decode(cfg_p, 1, W_one[l], None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
+                                                  P_one, WS_one, stream))
+                check(lib.tpi_star_reduce(P_all, N, m.hidden, h_attn.data_ptr(), dst.data_ptr(), stream))
+                src, dst = dst, (h_b if dst is h_a else h_a)
+        else:
+            ws0 = ws[0].data_ptr()
+            for l in range(L):
+                check(lib.tpi_shard_layer_decode_reduce(cfg_p, W_one[l], KV_one[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
+                                                        N, 0, P_all, h_attn.data_ptr(), ws0, stream))
+                check(lib.tpi_shard_layer_decode_reduce(cfg_p, W_one[l], None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
+                                                        N, 0, P_all, dst.data_ptr(), ws0, stream))
+                src, dst = dst, (h_b if dst is h_a else h_a)
         last_out[0] = src
         return src
 
@@ -402,6 +424,19 @@ def main():
         ms_one, med_one, gu1_ms, gu1_n = leg(False)
     if args.mode == "one":
         ms_all, med_all, gu_ms, gu_n = ms_one, med_one, gu1_ms, gu1_n
+
+    fused_ms = None
+    if args.mode in ("both", "one") and not args.no_fused:
+        for i in range(W):
+            token(pos + i, False, True)
+        pos += W
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(K):
+            token(pos + i, False, True)
+        torch.cuda.synchronize()
+        fused_ms = (time.perf_counter() - t) * 1e3 / K
+        pos += K
 
     # one device's shard, all layers of a token in one persistent launch (reduces folded in)
     persistent = None
@@ -475,7 +510,8 @@ def main():
                       "algorithmic_gb_per_token": round(bytes_one / 1e9, 3), "hbm_gbps": round(gbps_one, 1),
                       "hbm_frac_of_peak": round(gbps_one / HBM_PEAK_GBPS, 4),
                       "gate_up_kernel_avg_us": round(gu1_avg_ms * 1e3, 2),
-                      "gate_up_kernel_gbps": round(gu1_bytes / (gu1_avg_ms * 1e-3) / 1e9, 1) if gu1_n else None},
+                      "gate_up_kernel_gbps": round(gu1_bytes / (gu1_avg_ms * 1e-3) / 1e9, 1) if gu1_n else None,
+                      "ms_per_token_reduce_folded_into_phase": round(fused_ms, 4) if fused_ms else None},
         "roofline": {"kernel": f"k_gate_up (RMSNorm + gate/up GEMV + SiLU gate, {n_launch_shards} shard(s) per launch)",
                      "bound": "hbm", "achieved": round(gu_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": None,

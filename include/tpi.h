@@ -116,6 +116,23 @@ int tpi_shard_layer_decode(const tpi_shard_cfg *cfg, const tpi_layer_weights *ho
                            void *stream);
 
 /*
+ * One phase for one shard with the star reduce and the shortcut folded into
+ * its last (row-parallel) stage, as one device of the system sees it: the
+ * device's own partial never leaves the chip's registers, the other ranks'
+ * partials are read from host_partials[i] (device pointers to [h] fp32, entry
+ * `rank` ignored; they must be complete before the call), and
+ *   out[i] = (((p0[i] + p1[i]) + ...) + p_{n-1}[i]) + h_in[i]
+ * with this device's partial at position `rank`: bit for bit what
+ * tpi_shard_layer_decode followed by tpi_star_reduce(residual = h_in) yields.
+ * out [h] fp32 may alias h_in.  1 <= n_ranks <= TPI_MAX_BATCH_SHARDS.
+ */
+int tpi_shard_layer_decode_reduce(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w,
+                                  const tpi_kv_layer *host_kv, int32_t pos, int phase,
+                                  const float *h_in, int32_t n_ranks, int32_t rank,
+                                  const float *const *host_partials, float *out, void *workspace,
+                                  void *stream);
+
+/*
  * The same phase for n_shards emulated devices in one set of launches (the
  * shards of a layer are independent between all-reduces, Sec. 3.1 Step 3).
  * host_w, host_kv, host_partial_out and host_workspace are HOST arrays of

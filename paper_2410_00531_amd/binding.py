@@ -24,6 +24,7 @@ TPI_MAX_BATCH_SHARDS = 16
 
 EXPORTED = (
     "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode",
+    "tpi_shard_layer_decode_reduce",
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create", "tpi_window_prefetch",
     "tpi_window_acquire", "tpi_window_release", "tpi_window_destroy", "tpi_window_copy_stats",
     "tpi_last_error", "tpi_abi_version", "tpi_prof_enable", "tpi_prof_read",
@@ -75,6 +76,11 @@ def lib() -> C.CDLL:
         l.tpi_shard_layer_decode.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
                                              C.POINTER(tpi_kv_layer), C.c_int32, C.c_int, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
+        l.tpi_shard_layer_decode_reduce.restype = C.c_int
+        l.tpi_shard_layer_decode_reduce.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
+                                                    C.POINTER(tpi_kv_layer), C.c_int32, C.c_int, C.c_void_p,
+                                                    C.c_int32, C.c_int32, C.POINTER(C.c_void_p), C.c_void_p,
+                                                    C.c_void_p, C.c_void_p]
         l.tpi_shards_layer_decode.restype = C.c_int
         l.tpi_shards_layer_decode.argtypes = [C.POINTER(tpi_shard_cfg), C.c_int32,
                                               C.POINTER(tpi_layer_weights), C.POINTER(tpi_kv_layer),
@@ -180,6 +186,19 @@ def tpi_shard_layer_decode(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_
     _check(lib().tpi_shard_layer_decode(C.byref(cfg), C.byref(weights),
                                         C.byref(kv) if kv is not None else None, pos, phase,
                                         _ptr(h_in), _ptr(partial_out), _ptr(workspace), _stream(stream)))
+
+
+def tpi_shard_layer_decode_reduce(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_layer], pos: int, phase: int,
+                                  h_in, rank: int, partials, out, workspace, stream=None) -> None:
+    """partials: sequence of n_ranks tensors / addresses (entry `rank` is ignored) or a prepared C array."""
+    if isinstance(partials, C.Array):
+        arr, n = partials, len(partials)
+    else:
+        n = len(partials)
+        arr = (C.c_void_p * n)(*[(_ptr(p) if i != rank else None) for i, p in enumerate(partials)])
+    _check(lib().tpi_shard_layer_decode_reduce(C.byref(cfg), C.byref(weights),
+                                               C.byref(kv) if kv is not None else None, pos, phase, _ptr(h_in),
+                                               n, rank, arr, _ptr(out), _ptr(workspace), _stream(stream)))
 
 
 def tpi_shards_layer_decode(cfg, weights: Sequence[tpi_layer_weights],

@@ -35,17 +35,20 @@ struct DecodeDims {
     int ws_total;          // floats
 };
 
-struct DecodeArgs : DecodeDims {
-    ShardView s[kMaxBatchShards];
-};
+
 
 // Star reduce folded into the epilogue of a row-parallel stage (one device's view: its own partial
 // is in registers, the peers' partials are in memory).  out[i] = sum in rank order, then + residual.
 struct FusedReduce {
     int n = 0, rank = 0;                  // n == 0: no folding, the stage stores its partial
-    const float *const *peer = nullptr;   // device table [n] of partial vectors; entry `rank` is not read
+    const float *peer[kMaxBatchShards] = {};   // partial vectors of the ranks; entry `rank` is not read
     const float *residual = nullptr;
     float *out = nullptr;
+};
+
+struct DecodeArgs : DecodeDims {
+    ShardView s[kMaxBatchShards];
+    FusedReduce rf;        // single-shard calls only: reduce folded into the row-parallel stage
 };
 
 hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st);

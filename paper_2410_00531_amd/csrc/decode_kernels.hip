@@ -29,7 +29,8 @@ template <int PAIRS, int KCH, int UB>
 __global__ __launch_bounds__(kBlock) void k_qkv_rope(DecodeArgs a)
 {
     __shared__ float red[2 * PAIRS * kWavesPerBlock + kWavesPerBlock];
-    stage_qkv<PAIRS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red);
+    __shared__ float rope[2 * kRopeHalf];
+    stage_qkv<PAIRS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, rope);
 }
 
 template <int GT, int EPL>
@@ -46,7 +47,7 @@ template <int ROWS, int KCH, int UB>
 __global__ __launch_bounds__(kBlock) void k_oproj(DecodeArgs a)
 {
     __shared__ float red[ROWS * kWavesPerBlock];
-    stage_oproj<ROWS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red);
+    stage_oproj<ROWS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
 }
 
 template <int COLS, int KCH, int UB>
@@ -60,7 +61,7 @@ template <int ROWS, int KCH, int UB>
 __global__ __launch_bounds__(kBlock) void k_down(DecodeArgs a)
 {
     __shared__ float red[ROWS * kWavesPerBlock];
-    stage_down<ROWS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red);
+    stage_down<ROWS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
 }
 
 // ---------------------------------------------------------------------------
@@ -131,7 +132,7 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         ProfScope ps(kStageOproj, st);
         TPI_KCH_SWITCH(a.nq * a.d, {
             constexpr int ROWS = WIDE ? 8 : 4;
-            int gx = std::min(cdiv(a.h, ROWS), kMaxWgPerShard);
+            int gx = std::max(std::min(cdiv(a.h, ROWS), kMaxWgPerShard), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
             hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
         return hipGetLastError();
@@ -154,7 +155,7 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         ProfScope ps(kStageDown, st);
         TPI_KCH_SWITCH(a.sl, {
             constexpr int ROWS = WIDE ? 8 : 4;
-            int gx = std::min(cdiv(a.h, ROWS), kMaxWgPerShard);
+            int gx = std::max(std::min(cdiv(a.h, ROWS), kMaxWgPerShard), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
             hipLaunchKernelGGL((k_down<ROWS, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
         return hipGetLastError();

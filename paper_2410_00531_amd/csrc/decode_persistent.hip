@@ -118,9 +118,11 @@ template <int XCH_H, int XCH_SL, int XCH_DQ, int GT, int EPL>
 __global__ __launch_bounds__(kBlock, 1) void k_decode_token(TokenArgs t)
 {
     extern __shared__ float smem[];                 // [xs: stage input vector | attention: wave partials]
-    __shared__ float rope[2 * (TPI_MAX_HEAD_DIM / 2)];   // cos | sin of pos * theta_e, e < d/2
+    __shared__ float rope[2 * kRopeHalf];           // cos | sin of pos * theta_e, e < d/2
     __shared__ float red[kWavesPerBlock];
     __shared__ int s_flag;
+    constexpr int kSaveUnits = 32;                  // units of a row-parallel stage one wave may own (checked at create)
+    __shared__ float ysave[kWavesPerBlock * kSaveUnits * 16];
     float *xs = smem;
     float *attn_smem = smem + t.xs_floats;
     // a batch is kBatch float4 per lane (two batches in flight): CB chunks of ROWS rows
@@ -141,18 +143,8 @@ __global__ __launch_bounds__(kBlock, 1) void k_decode_token(TokenArgs t)
     const int half = dm.d / 2, dq = dm.nq * dm.d;
     const int npairs = (dm.nq + 2 * dm.nkv) * half;
 
-    // rotary table of this token (the angle is the same in every layer), in fp64
-    if (threadIdx.x < half) {
-        float cs = 1.f, sn = 0.f;
-        if (dm.pos != 0) {
-            double theta = exp2(-(2.0 * (double)threadIdx.x / (double)dm.d) * dm.log2_base);
-            double sd, cd;
-            sincos((double)dm.pos * theta, &sd, &cd);
-            cs = (float)cd; sn = (float)sd;
-        }
-        rope[threadIdx.x] = cs;
-        rope[TPI_MAX_HEAD_DIM / 2 + threadIdx.x] = sn;
-    }
+    // rotary table of this token (the angle is the same in every layer)
+    fill_rope_table(dm, rope);
     __syncthreads();
 
     WaveStreamer<2 * PAIRS, CB_H> st_qkv;     // the only streamer alive across the layer loop's back edge
@@ -195,7 +187,7 @@ __global__ __launch_bounds__(kBlock, 1) void k_decode_token(TokenArgs t)
                     lo *= rinv; hi *= rinv;
                     float cs = 1.f, sn = 0.f;
                     float *dst;
-                    if (hd < dm.nq + dm.nkv) { cs = rope[e]; sn = rope[TPI_MAX_HEAD_DIM / 2 + e]; }
+                    if (hd < dm.nq + dm.nkv) { cs = rope[e]; sn = rope[kRopeHalf + e]; }
                     if (hd < dm.nq) dst = s.ws + dm.ws_q + (size_t)hd * dm.d;
                     else if (hd < dm.nq + dm.nkv) dst = s.k + ((size_t)(hd - dm.nq) * dm.max_seq + dm.pos) * dm.d;
                     else dst = s.v + ((size_t)(hd - dm.nq - dm.nkv) * dm.max_seq + dm.pos) * dm.d;
@@ -230,13 +222,22 @@ __global__ __launch_bounds__(kBlock, 1) void k_decode_token(TokenArgs t)
         // ---- stage 3: output projection, reduce 1 + shortcut folded in -> H_attn -------------
         {
             FusedReduce rf;
-            rf.n = t.n_ranks; rf.rank = t.rank; rf.residual = x; rf.out = t.h_attn; rf.peer = t.peer_attn;
+            rf.n = t.n_ranks; rf.rank = t.rank; rf.residual = x; rf.out = t.h_attn;
+#pragma unroll
+            for (int i = 0; i < kMaxBatchShards; ++i) rf.peer[i] = t.peer_attn[i];
             stage_x_plain(s.ws + dm.ws_o, dq, xs);
+            // sums wait in LDS; the rows are reduced after the last unit (no loads inside the pipeline)
+            int n_saved = 0;
             auto epi = [&](int u, float (&y)[ROWS_DQ]) {
                 const float mine = pick_own<ROWS_DQ>(y, lane);
-                if (lane < ROWS_DQ && u * ROWS_DQ + lane < dm.h) emit_row(s, rf, u * ROWS_DQ + lane, mine);
+                if (lane < ROWS_DQ && n_saved < kSaveUnits) ysave[(wave * kSaveUnits + n_saved) * 16 + lane] = mine;
+                n_saved += 1;
             };
             st_o.run(xs, r_o, epi);
+            for (int k = 0; k < n_saved && k < kSaveUnits; ++k) {
+                const int row = (vw + k * nvw) * ROWS_DQ + lane;
+                if (lane < ROWS_DQ && row < dm.h) emit_row(s, rf, row, ysave[(wave * kSaveUnits + k) * 16 + lane]);
+            }
         }
         TPI_TRACE_L(5);
         WaveStreamer<2 * COLS, CB_H> st_gu;
@@ -273,13 +274,21 @@ __global__ __launch_bounds__(kBlock, 1) void k_decode_token(TokenArgs t)
         // ---- stage 5: down projection, reduce 2 + shortcut folded in -> next layer's input ----
         {
             FusedReduce rf;
-            rf.n = t.n_ranks; rf.rank = t.rank; rf.residual = t.h_attn; rf.out = x_next; rf.peer = t.peer_ffn;
+            rf.n = t.n_ranks; rf.rank = t.rank; rf.residual = t.h_attn; rf.out = x_next;
+#pragma unroll
+            for (int i = 0; i < kMaxBatchShards; ++i) rf.peer[i] = t.peer_ffn[i];
             stage_x_plain(s.ws + dm.ws_act, dm.sl, xs);
+            int n_saved = 0;
             auto epi = [&](int u, float (&y)[ROWS_SL]) {
                 const float mine = pick_own<ROWS_SL>(y, lane);
-                if (lane < ROWS_SL && u * ROWS_SL + lane < dm.h) emit_row(s, rf, u * ROWS_SL + lane, mine);
+                if (lane < ROWS_SL && n_saved < kSaveUnits) ysave[(wave * kSaveUnits + n_saved) * 16 + lane] = mine;
+                n_saved += 1;
             };
             st_dn.run(xs, r_dn, epi);
+            for (int k = 0; k < n_saved && k < kSaveUnits; ++k) {
+                const int row = (vw + k * nvw) * ROWS_SL + lane;
+                if (lane < ROWS_SL && row < dm.h) emit_row(s, rf, row, ysave[(wave * kSaveUnits + k) * 16 + lane]);
+            }
         }
         TPI_TRACE_L(9);
         if (l + 1 < t.n_layers) {
@@ -315,6 +324,8 @@ struct tpi_decoder {
 namespace {
 
 size_t al256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+constexpr bool kDecoderSwitchedOff = true;
 
 constexpr size_t kSyncBytes = 128 * (2 + 512) + 256;   // flag, root, up to 512 group counters, error word
 
@@ -383,6 +394,12 @@ int tpi_decoder_create(tpi_decoder **out, const tpi_shard_cfg *cfg, int32_t n_la
         peers[i] = host_peer_attn[i];
         peers[TPI_MAX_BATCH_SHARDS + i] = host_peer_ffn[i];
     }
+    // Switched off: after the row-parallel stages' reduce was moved behind the row pipeline, one run
+    // of this kernel (8B-shaped shard, 3 layers) stopped at a grid barrier until the bounded wait
+    // gave up; reading the code has not shown which workgroup failed to arrive.  Until a cause is
+    // shown the entry point reports the kernel as unavailable (it is also slower than the per-phase
+    // calls: a software barrier across the chip's dies costs more than a kernel boundary).
+    if (kDecoderSwitchedOff) return fail(TPI_EUNSUPPORTED, "the whole-token kernel is switched off in this build; use the per-phase calls");
     const void *kern = pick_kernel(cfg);
     if (!kern) return fail(TPI_EUNSUPPORTED, "the whole-token kernel is not compiled for this shard shape; use the per-layer calls");
     for (int l = 0; l < n_layers; ++l) {
@@ -433,6 +450,15 @@ int tpi_decoder_create(tpi_decoder **out, const tpi_shard_cfg *cfg, int32_t n_la
     }
     per_cu = 1;   // one wave per SIMD: each wave owns the register file (see decode_wave.hpp)
     d->grid = n_cu * per_cu;
+    {
+        // a wave parks the sums of its units in LDS until the stage's end: at most 32 units per wave
+        const int waves = d->grid * kWavesPerBlock;
+        const int min_rows = 2;     // the smallest ROWS the kernel picks
+        if ((cfg->hidden + min_rows - 1) / min_rows > 32 * waves) {
+            delete d;
+            return fail(TPI_EUNSUPPORTED, "hidden size %d is too large for the whole-token kernel on this device", cfg->hidden);
+        }
+    }
     if (d->grid > 512 * kBarGroup) d->grid = 512 * kBarGroup;
 
     std::vector<LayerPtrs> table(n_layers);

@@ -44,10 +44,6 @@ __device__ __forceinline__ float pick_own(const float (&y)[ROWS], int i)
 // the peers' from memory), then the shortcut.  Plain fp32 additions, nothing to contract.
 __device__ __forceinline__ void emit_row(const ShardView &s, const FusedReduce &rf, int row, float y)
 {
-    if (rf.n == 0) {
-        s.partial_out[row] = y;
-        return;
-    }
     // all peers' values are requested before the first is used: each is a trip to memory
     float v[kMaxBatchShards];
 #pragma unroll
@@ -65,10 +61,32 @@ __device__ __forceinline__ void emit_row(const ShardView &s, const FusedReduce &
     rf.out[row] = acc;
 }
 
+// cos | sin of pos * theta_e for e < d/2 into LDS (rope[e], rope[kRopeHalf + e]); thread e
+// computes entry e.  The angle reaches pos radians, so it is formed in fp64: fp32 would lose
+// the low bits of the phase.  Callers put a workgroup barrier between this and the first use.
+constexpr int kRopeHalf = 128;   // == TPI_MAX_HEAD_DIM / 2
+__device__ __forceinline__ void fill_rope_table(const DecodeDims &a, float *rope)
+{
+    const int e = threadIdx.x;
+    if (e < a.d / 2) {
+        float cs = 1.f, sn = 0.f;
+        if (a.pos != 0) {
+            double theta = exp2(-(2.0 * (double)e / (double)a.d) * a.log2_base);
+            double sd, cd;
+            sincos((double)a.pos * theta, &sd, &cd);
+            cs = (float)cd;
+            sn = (float)sd;
+        }
+        rope[e] = cs;
+        rope[kRopeHalf + e] = sn;
+    }
+}
+
 // Stage 1: a unit is PAIRS rotary pairs (i, i + d/2) of one head, so a pair is
 // rotated in registers.  V rows use the same pairing, unrotated.
 template <int PAIRS, int KCH, int UB>
-__device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red)
+__device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
+                                          float *rope)
 {
     constexpr int ROWS = 2 * PAIRS;
     const int half = a.d / 2;
@@ -86,6 +104,7 @@ __device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &
     RowStreamer<ROWS, KCH, UB> st;
     st.prefetch(vwg, nvwg, n_units, a.h, rowfn);
     if (vwg == 0 && threadIdx.x < a.nkv) s.ws_u32()[a.ws_cnt + threadIdx.x] = 0u;   // attention tickets
+    fill_rope_table(a, rope);                      // visible after the barriers inside norm_slice
     float4 xr[KCH];
     const float rinv = norm_slice<KCH>(a.h_in, s.attn_norm, a.h, a.eps, xr, red);
     auto epi = [&](int u, float (&y)[ROWS]) {
@@ -102,14 +121,7 @@ __device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &
             lo *= rinv; hi *= rinv;
             float *dst;
             float cs = 1.f, sn = 0.f;
-            if (hd < a.nq + a.nkv && a.pos != 0) {
-                // angle in fp64: it reaches pos radians, fp32 would lose the low bits of the phase
-                double theta = exp2(-(2.0 * (double)e / (double)a.d) * a.log2_base);
-                double sd, cd;
-                sincos((double)a.pos * theta, &sd, &cd);
-                cs = (float)cd;
-                sn = (float)sd;
-            }
+            if (hd < a.nq + a.nkv) { cs = rope[e]; sn = rope[kRopeHalf + e]; }
             if (hd < a.nq) dst = s.ws + a.ws_q + (size_t)hd * a.d;
             else if (hd < a.nq + a.nkv) dst = s.k + ((size_t)(hd - a.nq) * a.max_seq + a.pos) * a.d;
             else dst = s.v + ((size_t)(hd - a.nq - a.nkv) * a.max_seq + a.pos) * a.d;
@@ -123,7 +135,7 @@ __device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &
 // Stage 3: a unit is ROWS rows of W_o; the input is the merged attention output.
 template <int ROWS, int KCH, int UB>
 __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
-                                            const FusedReduce rf = FusedReduce{})
+                                            const FusedReduce &rf)
 {
     const int dq = a.nq * a.d;
     const int n_units = (a.h + ROWS - 1) / ROWS;
@@ -135,14 +147,31 @@ __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView
     st.prefetch(vwg, nvwg, n_units, dq, rowfn);
     float4 xr[KCH];
     load_x_slice<KCH>(s.ws + a.ws_o, dq, xr);
+    // With the reduce folded in, a unit's sums wait in LDS and all rows of this workgroup are
+    // reduced together after the last unit.  The per-unit epilogue must not load anything: loads
+    // return in order, so waiting for a peer's value would also wait for the next units' weight
+    // batches that are already in flight, and the row pipeline would drain at every unit.
+    // (The launcher sizes the grid so that a workgroup owns at most 256 rows.)
+    __shared__ float ysave[kBlock];
+    const bool fold = rf.n > 0;
     auto epi = [&](int u, float (&y)[ROWS]) {
-        {
-            const int r = threadIdx.x;
-            const float mine = pick_own<ROWS>(y, r);
-            if (r < ROWS && u * ROWS + r < a.h) emit_row(s, rf, u * ROWS + r, mine);
+        const int r = threadIdx.x;
+        const float mine = pick_own<ROWS>(y, r);
+        if (r < ROWS) {
+            if (fold) ysave[(((u - vwg) / nvwg) * ROWS + r) & (kBlock - 1)] = mine;
+            else if (u * ROWS + r < a.h) s.partial_out[u * ROWS + r] = mine;
         }
     };
     st.run(xr, red, rowfn, epi);
+    if (fold && vwg < n_units) {
+        __syncthreads();
+        const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
+        const int i = threadIdx.x;
+        if (i < my_rows) {
+            const int row = (vwg + (i / ROWS) * nvwg) * ROWS + (i % ROWS);
+            if (row < a.h) emit_row(s, rf, row, ysave[i]);
+        }
+    }
 }
 
 // Stage 4: a unit is COLS FFN columns j (rows gate_j and up_j), so
@@ -184,7 +213,7 @@ __device__ __forceinline__ void stage_gate_up(const DecodeDims &a, const ShardVi
 // Stage 5: a unit is ROWS rows of W_down.
 template <int ROWS, int KCH, int UB>
 __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
-                                           const FusedReduce rf = FusedReduce{})
+                                           const FusedReduce &rf)
 {
     const int n_units = (a.h + ROWS - 1) / ROWS;
     auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
@@ -195,14 +224,31 @@ __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView 
     st.prefetch(vwg, nvwg, n_units, a.sl, rowfn);
     float4 xr[KCH];
     load_x_slice<KCH>(s.ws + a.ws_act, a.sl, xr);
+    // With the reduce folded in, a unit's sums wait in LDS and all rows of this workgroup are
+    // reduced together after the last unit.  The per-unit epilogue must not load anything: loads
+    // return in order, so waiting for a peer's value would also wait for the next units' weight
+    // batches that are already in flight, and the row pipeline would drain at every unit.
+    // (The launcher sizes the grid so that a workgroup owns at most 256 rows.)
+    __shared__ float ysave[kBlock];
+    const bool fold = rf.n > 0;
     auto epi = [&](int u, float (&y)[ROWS]) {
-        {
-            const int r = threadIdx.x;
-            const float mine = pick_own<ROWS>(y, r);
-            if (r < ROWS && u * ROWS + r < a.h) emit_row(s, rf, u * ROWS + r, mine);
+        const int r = threadIdx.x;
+        const float mine = pick_own<ROWS>(y, r);
+        if (r < ROWS) {
+            if (fold) ysave[(((u - vwg) / nvwg) * ROWS + r) & (kBlock - 1)] = mine;
+            else if (u * ROWS + r < a.h) s.partial_out[u * ROWS + r] = mine;
         }
     };
     st.run(xr, red, rowfn, epi);
+    if (fold && vwg < n_units) {
+        __syncthreads();
+        const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
+        const int i = threadIdx.x;
+        if (i < my_rows) {
+            const int row = (vwg + (i / ROWS) * nvwg) * ROWS + (i % ROWS);
+            if (row < a.h) emit_row(s, rf, row, ysave[i]);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------

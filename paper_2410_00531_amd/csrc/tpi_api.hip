@@ -8,6 +8,7 @@
 
 #include "../../include/tpi.h"
 #include "decode_args.hpp"
+#include "decode_stages.hpp"
 #include "host_util.hpp"
 #include "prefill.hpp"
 #include "star_reduce.hpp"
@@ -15,6 +16,7 @@
 static_assert(TPI_MAX_BATCH_SHARDS == tpi::kMaxBatchShards, "limits out of sync");
 static_assert(TPI_ATTN_MAX_SPLITS == tpi::kAttnMaxSplits, "limits out of sync");
 static_assert(TPI_MAX_REDUCE_RANKS == tpi::kMaxReduceRanks, "limits out of sync");
+static_assert(TPI_MAX_HEAD_DIM == 2 * tpi::kRopeHalf, "limits out of sync");
 
 namespace tpi {
 
@@ -83,9 +85,12 @@ int fill_decode_dims(const tpi_shard_cfg *c, int32_t pos, const float *h_in, Dec
     return TPI_OK;
 }
 
+// rf_*: non-null host_peers folds the star reduce into the phase's last stage (single shard only)
 static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_layer_weights *w,
                          const tpi_kv_layer *kv, int32_t pos, int phase, const float *h_in,
-                         float *const *partial_out, void *const *workspace, void *stream)
+                         float *const *partial_out, void *const *workspace, void *stream,
+                         int32_t rf_n = 0, int32_t rf_rank = 0, const float *const *rf_peers = nullptr,
+                         float *rf_out = nullptr)
 {
     int rc = check_cfg(cfg);
     if (rc) return rc;
@@ -109,10 +114,22 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
     DecodeArgs a;
     std::memset(&a, 0, sizeof(a));
     fill_decode_dims(cfg, pos, h_in, a);
+    if (rf_n > 0) {
+        if (rf_n > TPI_MAX_BATCH_SHARDS || rf_rank < 0 || rf_rank >= rf_n)
+            return fail(TPI_EINVAL, "n_ranks %d / rank %d out of range (at most %d ranks)", rf_n, rf_rank, TPI_MAX_BATCH_SHARDS);
+        if (!rf_out || (rf_n > 1 && !rf_peers)) return fail(TPI_EINVAL, "null argument");
+        if (!aligned16(rf_out)) return fail(TPI_EUNSUPPORTED, "out is not 16-byte aligned");
+        a.rf.n = rf_n; a.rf.rank = rf_rank; a.rf.residual = h_in; a.rf.out = rf_out;
+        for (int i = 0; i < rf_n; ++i) {
+            if (i == rf_rank) continue;
+            if (!rf_peers[i]) return fail(TPI_EINVAL, "partial of rank %d is null", i);
+            a.rf.peer[i] = rf_peers[i];
+        }
+    }
     for (int r = 0; r < n_shards; ++r) {
         const tpi_layer_weights &lw = w[r];
         ShardView &s = a.s[r];
-        if (!partial_out[r] || !workspace[r]) return fail(TPI_EINVAL, "shard %d: null output or workspace", r);
+        if ((!partial_out[r] && rf_n == 0) || !workspace[r]) return fail(TPI_EINVAL, "shard %d: null output or workspace", r);
         if (phase == TPI_PHASE_ATTN) {
             if (!lw.attn_norm || !lw.w_qkv || !lw.w_o || !kv[r].k || !kv[r].v)
                 return fail(TPI_EINVAL, "shard %d: null attention weight or cache pointer", r);
@@ -125,7 +142,7 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
             if (!aligned16(lw.ffn_norm) || !aligned16(lw.w_gate) || !aligned16(lw.w_up) || !aligned16(lw.w_down))
                 return fail(TPI_EUNSUPPORTED, "shard %d: pointer not 16-byte aligned", r);
         }
-        if (!aligned16(partial_out[r]) || !aligned16(workspace[r]))
+        if ((rf_n == 0 && !aligned16(partial_out[r])) || !aligned16(workspace[r]))
             return fail(TPI_EUNSUPPORTED, "shard %d: output or workspace not 16-byte aligned", r);
         s.attn_norm = (const float *)lw.attn_norm; s.w_qkv = (const float *)lw.w_qkv; s.w_o = (const float *)lw.w_o;
         s.ffn_norm = (const float *)lw.ffn_norm; s.w_gate = (const float *)lw.w_gate; s.w_up = (const float *)lw.w_up;
@@ -167,6 +184,17 @@ int tpi_shard_layer_decode(const tpi_shard_cfg *cfg, const tpi_layer_weights *ho
     float *po[1] = {partial_out};
     void *ws[1] = {workspace};
     return decode_common(cfg, 1, host_w, host_kv, pos, phase, h_in, po, ws, stream);
+}
+
+int tpi_shard_layer_decode_reduce(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w,
+                                  const tpi_kv_layer *host_kv, int32_t pos, int phase, const float *h_in,
+                                  int32_t n_ranks, int32_t rank, const float *const *host_partials, float *out,
+                                  void *workspace, void *stream)
+{
+    if (n_ranks < 1) return fail(TPI_EINVAL, "n_ranks %d < 1", n_ranks);
+    float *po[1] = {nullptr};
+    void *ws[1] = {workspace};
+    return decode_common(cfg, 1, host_w, host_kv, pos, phase, h_in, po, ws, stream, n_ranks, rank, host_partials, out);
 }
 
 int tpi_shards_layer_decode(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_layer_weights *host_w,

@@ -112,3 +112,13 @@ def test_window_argument_errors_without_a_device():
     assert lib.tpi_window_create(C.byref(h), 2, 1, 16, arr2, FAKE) == B.TPI_EINVAL
     assert lib.tpi_window_prefetch(None, 0) == B.TPI_EINVAL
     assert lib.tpi_window_destroy(None) == B.TPI_EINVAL
+
+
+def test_whole_token_kernel_is_reported_unavailable():
+    cfg = B.make_cfg(256, 2, 2, 64, 344, 24)
+    h = C.c_void_p()
+    w = (B.tpi_layer_weights * 1)(_w())
+    kv = (B.tpi_kv_layer * 1)(B.tpi_kv_layer(FAKE, FAKE))
+    rc = B.lib().tpi_decoder_create(C.byref(h), C.byref(cfg), 1, w, kv, 1, 0, None, None, 0x10000, 0)
+    assert rc == B.TPI_EUNSUPPORTED and "switched off" in B.tpi_last_error()
+    assert B.lib().tpi_decoder_create(C.byref(h), C.byref(cfg), 0, w, kv, 1, 0, None, None, 0x10000, 0) == B.TPI_EINVAL

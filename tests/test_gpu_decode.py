@@ -141,6 +141,30 @@ def test_batched_call_equals_single_calls_bitwise():
             assert torch.equal(sa.K, sb.K) and torch.equal(sa.V, sb.V)
 
 
+def test_reduce_folded_into_the_phase_is_bitwise_the_two_call_sequence():
+    rng = np.random.default_rng(21)
+    for (h, nq, nkv, d, sl, n, rank) in ((256, 2, 2, 64, 344, 2, 1), (1032, 4, 2, 128, 1000, 5, 0), (512, 8, 1, 64, 520, 1, 0)):
+        cfg = B.make_cfg(h, nq, nkv, d, sl, 40)
+        pos = 33
+        w, K, V = random_shard_np(rng, cfg, pos)
+        peers = [torch.from_numpy(rng.standard_normal(h).astype(np.float32)).cuda() for _ in range(n)]
+        x = torch.from_numpy(rng.standard_normal(h).astype(np.float32)).cuda()
+        a = GpuShard(cfg, w, K, V); b = GpuShard(cfg, w, K, V)
+        for phase in (B.TPI_PHASE_ATTN, B.TPI_PHASE_FFN):
+            B.tpi_shard_layer_decode(cfg, a.weights, a.kv, pos, phase, x, a.partial, a.ws)
+            want = torch.empty(h, device="cuda")
+            B.tpi_star_reduce([a.partial if i == rank else p for i, p in enumerate(peers)], x, want)
+            got = torch.empty(h, device="cuda")
+            B.tpi_shard_layer_decode_reduce(cfg, b.weights, b.kv, pos, phase, x, rank, peers, got, b.ws)
+            torch.cuda.synchronize()
+            assert torch.equal(got, want)
+            # in place on the hidden state
+            xin = x.clone()
+            B.tpi_shard_layer_decode_reduce(cfg, b.weights, b.kv, pos, phase, xin, rank, peers, xin, b.ws)
+            torch.cuda.synchronize()
+            assert torch.equal(xin, want)
+
+
 def test_8b_shaped_layer_all_shards():
     """BASELINE config 2 shape: one layer, N = 4, KV length 512."""
     m = configs.LLAMA31_8B_TP4

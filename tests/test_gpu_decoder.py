@@ -10,7 +10,12 @@ from paper_2410_00531_amd import binding as B
 from paper_2410_00531_amd import configs, synth
 from tpi_testlib import FP32_TOL, GpuShard, ocfg, rel_err
 
-pytestmark = pytest.mark.gpu
+pytestmark = [
+    pytest.mark.gpu,
+    pytest.mark.skip(reason="the whole-token kernel is switched off (tpi_decoder_create returns TPI_EUNSUPPORTED): "
+                            "one run of the 8B-shaped case stopped at a grid barrier until its bounded wait gave up, "
+                            "and the cause has not been shown yet; see DESIGN.md"),
+]
 
 
 def _setup(m, n_layers, pos, max_seq, seed, n_ranks, rank):
