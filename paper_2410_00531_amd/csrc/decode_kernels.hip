@@ -43,11 +43,11 @@ __global__ __launch_bounds__(kBlock) void k_attn(DecodeArgs a)
     stage_attn<GT, EPL>(a, a.s[blockIdx.z], blockIdx.x, g, ht, smem);
 }
 
-template <int ROWS, int KCH, int UB>
+template <int ROWS, int KCH, int UB, bool FOLD>
 __global__ __launch_bounds__(kBlock) void k_oproj(DecodeArgs a)
 {
     __shared__ float red[ROWS * kWavesPerBlock];
-    stage_oproj<ROWS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
+    stage_oproj<ROWS, KCH, UB, FOLD>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
 }
 
 template <int COLS, int KCH, int UB>
@@ -57,11 +57,11 @@ __global__ __launch_bounds__(kBlock) void k_gate_up(DecodeArgs a)
     stage_gate_up<COLS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red);
 }
 
-template <int ROWS, int KCH, int UB>
+template <int ROWS, int KCH, int UB, bool FOLD>
 __global__ __launch_bounds__(kBlock) void k_down(DecodeArgs a)
 {
     __shared__ float red[ROWS * kWavesPerBlock];
-    stage_down<ROWS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
+    stage_down<ROWS, KCH, UB, FOLD>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
 }
 
 // ---------------------------------------------------------------------------
@@ -133,7 +133,8 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         TPI_KCH_SWITCH(a.nq * a.d, {
             constexpr int ROWS = WIDE ? 8 : 4;
             int gx = std::max(std::min(cdiv(a.h, ROWS), kMaxWgPerShard), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
-            hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            if (a.rf.n > 0) hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, true>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            else hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, false>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
         return hipGetLastError();
     }
@@ -156,7 +157,8 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         TPI_KCH_SWITCH(a.sl, {
             constexpr int ROWS = WIDE ? 8 : 4;
             int gx = std::max(std::min(cdiv(a.h, ROWS), kMaxWgPerShard), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
-            hipLaunchKernelGGL((k_down<ROWS, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            if (a.rf.n > 0) hipLaunchKernelGGL((k_down<ROWS, KCH, UB, true>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            else hipLaunchKernelGGL((k_down<ROWS, KCH, UB, false>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
         return hipGetLastError();
     }

@@ -133,7 +133,7 @@ __device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &
 }
 
 // Stage 3: a unit is ROWS rows of W_o; the input is the merged attention output.
-template <int ROWS, int KCH, int UB>
+template <int ROWS, int KCH, int UB, bool FOLD>
 __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
                                             const FusedReduce &rf)
 {
@@ -153,17 +153,20 @@ __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView
     // batches that are already in flight, and the row pipeline would drain at every unit.
     // (The launcher sizes the grid so that a workgroup owns at most 256 rows.)
     __shared__ float ysave[kBlock];
-    const bool fold = rf.n > 0;
+    constexpr bool fold = FOLD;      // compile-time: the plain stage carries none of the folding code
     auto epi = [&](int u, float (&y)[ROWS]) {
-        const int r = threadIdx.x;
-        const float mine = pick_own<ROWS>(y, r);
-        if (r < ROWS) {
-            if (fold) ysave[(((u - vwg) / nvwg) * ROWS + r) & (kBlock - 1)] = mine;
-            else if (u * ROWS + r < a.h) s.partial_out[u * ROWS + r] = mine;
+        if constexpr (fold) {
+            const int r = threadIdx.x;
+            const float mine = pick_own<ROWS>(y, r);
+            if (r < ROWS) ysave[(((u - vwg) / nvwg) * ROWS + r) & (kBlock - 1)] = mine;
+        } else {
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r)
+                if (threadIdx.x == r && u * ROWS + r < a.h) s.partial_out[u * ROWS + r] = y[r];
         }
     };
     st.run(xr, red, rowfn, epi);
-    if (fold && vwg < n_units) {
+    if constexpr (fold) if (vwg < n_units) {
         __syncthreads();
         const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
         const int i = threadIdx.x;
@@ -211,7 +214,7 @@ __device__ __forceinline__ void stage_gate_up(const DecodeDims &a, const ShardVi
 }
 
 // Stage 5: a unit is ROWS rows of W_down.
-template <int ROWS, int KCH, int UB>
+template <int ROWS, int KCH, int UB, bool FOLD>
 __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
                                            const FusedReduce &rf)
 {
@@ -230,17 +233,20 @@ __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView 
     // batches that are already in flight, and the row pipeline would drain at every unit.
     // (The launcher sizes the grid so that a workgroup owns at most 256 rows.)
     __shared__ float ysave[kBlock];
-    const bool fold = rf.n > 0;
+    constexpr bool fold = FOLD;      // compile-time: the plain stage carries none of the folding code
     auto epi = [&](int u, float (&y)[ROWS]) {
-        const int r = threadIdx.x;
-        const float mine = pick_own<ROWS>(y, r);
-        if (r < ROWS) {
-            if (fold) ysave[(((u - vwg) / nvwg) * ROWS + r) & (kBlock - 1)] = mine;
-            else if (u * ROWS + r < a.h) s.partial_out[u * ROWS + r] = mine;
+        if constexpr (fold) {
+            const int r = threadIdx.x;
+            const float mine = pick_own<ROWS>(y, r);
+            if (r < ROWS) ysave[(((u - vwg) / nvwg) * ROWS + r) & (kBlock - 1)] = mine;
+        } else {
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r)
+                if (threadIdx.x == r && u * ROWS + r < a.h) s.partial_out[u * ROWS + r] = y[r];
         }
     };
     st.run(xr, red, rowfn, epi);
-    if (fold && vwg < n_units) {
+    if constexpr (fold) if (vwg < n_units) {
         __syncthreads();
         const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
         const int i = threadIdx.x;
