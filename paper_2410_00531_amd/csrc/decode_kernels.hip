@@ -80,6 +80,14 @@ static inline int kch_of(int K)
 
 constexpr int kMaxWgPerShard = 1024;   // workgroups one shard's stage is dealt to (4 per CU)
 
+// Workgroups for n_units units: at most kMaxWgPerShard, and every workgroup gets the same number
+// of units (up to one), so the stage does not end with half the grid idle.
+static inline int balanced_grid(int n_units)
+{
+    int per = cdiv(n_units, kMaxWgPerShard);
+    return cdiv(n_units, per);
+}
+
 #define TPI_KCH_SWITCH(K, ...)                                      \
     switch (kch_of(K)) {                                            \
     case 1: { constexpr int KCH = 1, UB = 1, WIDE = 1; __VA_ARGS__; } break;  \
@@ -112,8 +120,8 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         const int npairs = (a.nq + 2 * a.nkv) * (a.d / 2);
         ProfScope ps(kStageQkv, st);
         TPI_KCH_SWITCH(a.h, {
-            constexpr int PAIRS = WIDE ? 4 : 2;
-            int gx = std::min(cdiv(npairs, PAIRS), kMaxWgPerShard);
+            constexpr int PAIRS = WIDE ? 4 : 1;
+            int gx = balanced_grid(cdiv(npairs, PAIRS));
             hipLaunchKernelGGL((k_qkv_rope<PAIRS, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
         hipError_t e = hipGetLastError();
@@ -132,7 +140,7 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         ProfScope ps(kStageOproj, st);
         TPI_KCH_SWITCH(a.nq * a.d, {
             constexpr int ROWS = WIDE ? 8 : 4;
-            int gx = std::max(std::min(cdiv(a.h, ROWS), kMaxWgPerShard), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
+            int gx = std::max(balanced_grid(cdiv(a.h, ROWS)), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
             if (a.rf.n > 0) hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, true>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
             else hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, false>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
@@ -146,7 +154,7 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         ProfScope ps(kStageGateUp, st);
         TPI_KCH_SWITCH(a.h, {
             constexpr int COLS = WIDE ? 4 : 2;
-            int gx = std::min(cdiv(a.sl, COLS), kMaxWgPerShard);
+            int gx = balanced_grid(cdiv(a.sl, COLS));
             hipLaunchKernelGGL((k_gate_up<COLS, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
         hipError_t e = hipGetLastError();
@@ -156,7 +164,7 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         ProfScope ps(kStageDown, st);
         TPI_KCH_SWITCH(a.sl, {
             constexpr int ROWS = WIDE ? 8 : 4;
-            int gx = std::max(std::min(cdiv(a.h, ROWS), kMaxWgPerShard), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
+            int gx = std::max(balanced_grid(cdiv(a.h, ROWS)), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
             if (a.rf.n > 0) hipLaunchKernelGGL((k_down<ROWS, KCH, UB, true>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
             else hipLaunchKernelGGL((k_down<ROWS, KCH, UB, false>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
