@@ -333,6 +333,150 @@ __global__ __launch_bounds__(256) void k_prefill_attn(const bf16_t *__restrict__
 }
 
 // ---------------------------------------------------------------------------
+// Causal GQA attention on the matrix cores (head_dim a multiple of 32, at most 128)
+// ---------------------------------------------------------------------------
+// Rows are the (token, query head of the group) pairs of one KV head, row = token * G + head.
+// A wave owns 32 rows and walks the key tiles (32 slots) its rows may see; the four waves of a
+// workgroup own consecutive row tiles and share the V tile through LDS.
+//
+// Scores are formed transposed, S^T[key][row] = K . Q^T: both operands are then read along the
+// head dimension, straight from global memory, and a lane ends up with 16 scores of ONE row
+// (its column), so the running softmax is in-lane work plus one exchange between the two
+// half-waves.  O^T[e][row] += V^T[e][key] . P^T[key][row]: P^T is exactly the score registers
+// (cast to bf16), no data movement; V^T is read from an LDS tile laid out [key / 4][e][key % 4],
+// in the key order the score registers hold (the contraction index may be permuted as long as
+// both operands agree).
+template <int D>
+__global__ __launch_bounds__(256) void k_prefill_attn_mfma(const bf16_t *__restrict__ q, const bf16_t *__restrict__ Kc,
+                                                           const bf16_t *__restrict__ Vc, bf16_t *__restrict__ o, int n,
+                                                           int nq, int nkv, int max_seq, int pos0)
+{
+    constexpr int ET = D / 32, KS = D / 16, TK = 32;
+    __shared__ __attribute__((aligned(16))) bf16_t Vt[(TK / 4) * D * 4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, hb = lane >> 5;
+    const int G = nq / nkv, gk = blockIdx.y;
+    const int n_rows = n * G;
+    const int row = (blockIdx.x * 4 + wave) * 32 + col;          // this lane's row (a column of S^T)
+    const bool row_ok = row < n_rows;
+    const int tok = row_ok ? row / G : n - 1, head = gk * G + (row_ok ? row % G : 0);
+    const int my_last = pos0 + tok;                               // last slot this row attends to
+    const int wave_first_row = (blockIdx.x * 4 + wave) * 32;
+    const int wave_last_tok = min(n - 1, (wave_first_row + 31) / G);
+    const int wg_last_tok = min(n - 1, ((blockIdx.x * 4 + 3) * 32 + 31) / G);
+    const bool wave_ok = wave_first_row < n_rows;
+    const int wave_last_key = pos0 + wave_last_tok, wg_last_key = pos0 + wg_last_tok;
+    const float scale = 1.0f / sqrtf((float)D);
+    const bf16_t *Kg = Kc + (size_t)gk * max_seq * D;
+    const bf16_t *Vg = Vc + (size_t)gk * max_seq * D;
+
+    bf16x8 qf[KS];
+    {
+        const bf16_t *qp = q + ((size_t)tok * nq + head) * D + hb * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+    }
+    f32x16 oacc[ET];
+#pragma unroll
+    for (int et = 0; et < ET; ++et)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[et][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    for (int k0 = 0; k0 <= wg_last_key; k0 += TK) {
+        __syncthreads();
+        // V tile -> LDS, transposed into [key / 4][e][key % 4]
+        for (int c = tid; c < TK * (D / 8); c += 256) {
+            int key = c / (D / 8), e0 = (c - key * (D / 8)) * 8;
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (k0 + key <= wg_last_key) raw = *reinterpret_cast<const uint4 *>(Vg + (size_t)(k0 + key) * D + e0);
+            const bf16_t *ev = reinterpret_cast<const bf16_t *>(&raw);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) Vt[((key >> 2) * D + e0 + i) * 4 + (key & 3)] = ev[i];
+        }
+        __syncthreads();
+        if (!wave_ok || k0 > wave_last_key) continue;
+
+        // S^T tile: rows of the MFMA = keys k0 .. k0+31, columns = this wave's 32 rows
+        f32x16 sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        {
+            const int key = min(k0 + col, wg_last_key);           // clamped: masked below
+            const bf16_t *kp = Kg + (size_t)key * D + hb * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kp + ks * 16);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
+            }
+        }
+        // register r of this lane: key k0 + 8*(r/4) + 4*hb + r%4, row = this lane's column
+        float mt = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            int key = k0 + 8 * (r >> 2) + 4 * hb + (r & 3);
+            float sv = (key <= my_last) ? sacc[r] * scale : -INFINITY;
+            sacc[r] = sv;
+            mt = fmaxf(mt, sv);
+        }
+        mt = fmaxf(mt, __shfl_xor(mt, 32, 64));                   // the other half-wave holds the row's other keys
+        const float m_new = fmaxf(m_run, mt);
+        float ls = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float p = (sacc[r] == -INFINITY) ? 0.f : __expf(sacc[r] - m_new);
+            sacc[r] = p;
+            ls += p;
+        }
+        ls += __shfl_xor(ls, 32, 64);
+        const float alpha = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+        l_run = l_run * alpha + ls;
+        if (m_new != -INFINITY) m_run = m_new;
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[et][r] *= alpha;
+        // P^T fragments: registers 8s .. 8s+7 are the 8 keys this half-wave contributes to MFMA step s
+        bf16x8 pf[2];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            union { bf16x8 v; bf16_t u[8]; } cvt;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) cvt.u[i] = f32_to_bf16(sacc[8 * s2 + i]);
+            pf[s2] = cvt.v;
+        }
+#pragma unroll
+        for (int et = 0; et < ET; ++et) {
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                // element i of the fragment: key 16*s2 + 8*(i/4) + 4*hb + i%4 -> groups 4*s2 + hb and 4*s2 + 2 + hb
+                union { bf16x8 v; uint2 h[2]; } vf;
+                const int e = et * 32 + col;
+                vf.h[0] = *reinterpret_cast<const uint2 *>(Vt + ((4 * s2 + hb) * D + e) * 4);
+                vf.h[1] = *reinterpret_cast<const uint2 *>(Vt + ((4 * s2 + 2 + hb) * D + e) * 4);
+                oacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[s2], oacc[et], 0, 0, 0);
+            }
+        }
+    }
+
+    if (row_ok) {
+        const float inv = 1.0f / l_run;
+        bf16_t *op = o + ((size_t)tok * nq + head) * D;
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                // registers 4*r4 .. 4*r4+3: elements e = 32*et + 8*r4 + 4*hb + 0..3
+                union { uint2 v; bf16_t u[4]; } pk;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pk.u[i] = f32_to_bf16(oacc[et][4 * r4 + i] * inv);
+                *reinterpret_cast<uint2 *>(op + 32 * et + 8 * r4 + 4 * hb) = pk.v;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
 namespace {
@@ -417,29 +561,40 @@ int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi
         hipLaunchKernelGGL(k_rope_scatter, dim3((nthr + 255) / 256), dim3(256), 0, st, big, qb, (bf16_t *)kv->k,
                            (bf16_t *)kv->v, n, nq, nkv, d, c->max_seq, pos0, std::log2((double)c->rope_base));
         TPI_LAUNCH_OK();
-        const int QT = 64 / G;                         // tokens per workgroup: QT * G <= 64 rows
-        const size_t lds = sizeof(float) * ((size_t)64 * (d + 1) + (size_t)64 * d + (size_t)64 * (d + 1) + 64 * 65);
-        dim3 grid((n + QT - 1) / QT, nkv);
-        if (lds > 65536) {                             // opt in to more than 64 KB of LDS per workgroup
-            int dev = 0, cap = 0;
-            e = hipGetDevice(&dev);
-            if (e == hipSuccess) e = hipDeviceGetAttribute(&cap, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
-            if (e != hipSuccess) return fail(TPI_ERUNTIME, "device query failed: %s", hipGetErrorString(e));
-            if ((size_t)cap < lds) return fail(TPI_EUNSUPPORTED, "attention tile needs %zu bytes of LDS, device allows %d", lds, cap);
-            e = (d <= 64) ? hipFuncSetAttribute((const void *)k_prefill_attn<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                          : hipFuncSetAttribute((const void *)k_prefill_attn<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return fail(TPI_ERUNTIME, "hipFuncSetAttribute: %s", hipGetErrorString(e));
-        }
-        if (d <= 64) {
-            hipLaunchKernelGGL((k_prefill_attn<64>), grid, dim3(256), lds, st, qb, (const bf16_t *)kv->k,
-                               (const bf16_t *)kv->v, ob, n, nq, nkv, d, c->max_seq, pos0, QT);
-        } else if (d <= 128) {
-            hipLaunchKernelGGL((k_prefill_attn<128>), grid, dim3(256), lds, st, qb, (const bf16_t *)kv->k,
-                               (const bf16_t *)kv->v, ob, n, nq, nkv, d, c->max_seq, pos0, QT);
+        if (d % 32 == 0 && d <= 128) {
+            dim3 grid((n * G + 127) / 128, nkv);
+            switch (d) {
+            case 32: hipLaunchKernelGGL((k_prefill_attn_mfma<32>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
+            case 64: hipLaunchKernelGGL((k_prefill_attn_mfma<64>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
+            case 96: hipLaunchKernelGGL((k_prefill_attn_mfma<96>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
+            default: hipLaunchKernelGGL((k_prefill_attn_mfma<128>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
+            }
+            TPI_LAUNCH_OK();
         } else {
-            return fail(TPI_EUNSUPPORTED, "prefill attention is built for head_dim <= 128");
+            const int QT = 64 / G;                         // tokens per workgroup: QT * G <= 64 rows
+            const size_t lds = sizeof(float) * ((size_t)64 * (d + 1) + (size_t)64 * d + (size_t)64 * (d + 1) + 64 * 65);
+            dim3 grid((n + QT - 1) / QT, nkv);
+            if (lds > 65536) {                             // opt in to more than 64 KB of LDS per workgroup
+                int dev = 0, cap = 0;
+                e = hipGetDevice(&dev);
+                if (e == hipSuccess) e = hipDeviceGetAttribute(&cap, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+                if (e != hipSuccess) return fail(TPI_ERUNTIME, "device query failed: %s", hipGetErrorString(e));
+                if ((size_t)cap < lds) return fail(TPI_EUNSUPPORTED, "attention tile needs %zu bytes of LDS, device allows %d", lds, cap);
+                e = (d <= 64) ? hipFuncSetAttribute((const void *)k_prefill_attn<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                              : hipFuncSetAttribute((const void *)k_prefill_attn<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e != hipSuccess) return fail(TPI_ERUNTIME, "hipFuncSetAttribute: %s", hipGetErrorString(e));
+            }
+            if (d <= 64) {
+                hipLaunchKernelGGL((k_prefill_attn<64>), grid, dim3(256), lds, st, qb, (const bf16_t *)kv->k,
+                                   (const bf16_t *)kv->v, ob, n, nq, nkv, d, c->max_seq, pos0, QT);
+            } else if (d <= 128) {
+                hipLaunchKernelGGL((k_prefill_attn<128>), grid, dim3(256), lds, st, qb, (const bf16_t *)kv->k,
+                                   (const bf16_t *)kv->v, ob, n, nq, nkv, d, c->max_seq, pos0, QT);
+            } else {
+                return fail(TPI_EUNSUPPORTED, "prefill attention is built for head_dim <= 128");
+            }
+            TPI_LAUNCH_OK();
         }
-        TPI_LAUNCH_OK();
         e = launch_gemm(ob, dq, (const bf16_t *)w->w_o, (const bf16_t *)w->w_o, h, dq, partial_out, h, n, h, dq, st);
         if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
     } else {

@@ -69,6 +69,9 @@ def _run_prefill_case(h, nq, nkv, d, sl, n, pos0, max_seq, seed, attn_scale=1.0)
     (264, 4, 1, 128, 72, 129, 3),      # K not a multiple of 64, group of 4, ragged everything
     (512, 8, 1, 128, 256, 64, 0),      # the 70B head layout: 8 query heads on one KV head
     (128, 3, 3, 32, 64, 200, 0),       # small heads, several key tiles
+    (192, 2, 1, 96, 64, 45, 2),        # head_dim 96: three 32-wide output tiles
+    (96, 4, 2, 48, 40, 33, 0),         # head_dim not a multiple of 32: the vector-ALU attention
+    (512, 16, 1, 64, 128, 150, 1),     # 16 query heads per KV head: a row tile covers two tokens
 ])
 def test_prefill_parity_small_shapes(h, nq, nkv, d, sl, n, pos0):
     _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + 3, seed=h + n + pos0, attn_scale=4.0)
