@@ -9,7 +9,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
+#include <type_traits>
 
 #include "host_util.hpp"
 #include "prof.hpp"
@@ -19,6 +21,17 @@ namespace tpi {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef unsigned short bf16_t;   // storage type
+
+// Development aid, compiled in only with -DTPI_TRACE: thread 0 of a workgroup stamps the 100 MHz wall clock.
+#ifdef TPI_TRACE
+__device__ unsigned long long g_ptrace[1 << 14];
+#define TPI_PTRACE(wg, slot)                                                                 \
+    do {                                                                                     \
+        if (threadIdx.x == 0 && (wg) < 1024) g_ptrace[(wg) * 16 + (slot)] = wall_clock64();  \
+    } while (0)
+#else
+#define TPI_PTRACE(wg, slot) do { } while (0)
+#endif
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((unsigned)v << 16); }
 
@@ -75,60 +88,104 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bf16(const bf16_t *__restrict__
 // C[m][n] = sum_k A[m][k] * B[n][k]   (bf16 in, fp32 out; both operands K-contiguous)
 // ---------------------------------------------------------------------------
 // Rows n < n_split of B come from B0, the rest from B1 (gate | up share one launch).
-// Workgroup tile BM x BN, 4 waves as 2 x 2, each wave (BM/2) x (BN/2) in 32x32 MFMA
-// tiles; K advances in steps of 64 through LDS (rows padded by 8 elements so the
-// 16-byte fragment reads of 8 consecutive lanes fall into distinct bank groups),
-// the next K-step's global loads are in flight while the current one is multiplied.
+// Workgroup tile BM x BN, 4 waves as 2 x 2, each wave (BM/2) x (BN/2) in 32x32 MFMA tiles.
+// K advances in steps of 64.  Step t is multiplied out of LDS stage (t+1) & 1 while the global
+// loads of steps t+1 .. t+NS sit in a ring of NS register sets (set = step % NS); at the end of
+// the step, set (t+1) % NS goes to the other LDS stage, one workgroup barrier per step.  With
+// one workgroup per compute unit nothing else hides the latency of HBM, hence the deep ring.
+// An LDS row is 64 elements = 8 chunks of 16 bytes, stored at
+// chunk position (chunk ^ (row & 7)): the fragment reads of 8 consecutive rows then cover all
+// banks without padding.
+// blockIdx.z selects a K range (split-K): split z writes its partial product to C + z * c_split
+// and the consumer adds the partials in split order.
 struct GemmArgs {
     const bf16_t *A;
     const bf16_t *B0, *B1;
     float *C;
     int M, N, K, n_split;
     int lda, ldb, ldc;
+    int k_per_split;          // multiple of 64
+    size_t c_split;           // floats between the partial products of consecutive splits
 };
 
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void k_gemm_bf16_nt(GemmArgs g)
-{
-    constexpr int BK = 64, LDT = BK + 8;
-    constexpr int MI = BM / 64, NI = BN / 64;           // 32x32 tiles per wave along m and n
-    constexpr int ACH = BM * (BK / 8) / 256;            // 16-byte chunks per thread, A tile
-    constexpr int BCH = BN * (BK / 8) / 256;
-    __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDT];
-    __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDT];
+// KW = 2: eight waves; waves 4..7 repeat the 2 x 2 arrangement and take the second half of every
+// K-step (a second wave per SIMD, so one wave's LDS and barrier waits are covered by the other's
+// MFMAs); their accumulators are added to those of waves 0..3 through LDS at the end.
+constexpr int kSwzShift = 1;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <int BM, int BN, int NS, int KW>
+__global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
+{
+    constexpr int BK = 64, NT = 256 * KW;
+    constexpr int MI = BM / 64, NI = BN / 64;           // 32x32 tiles per wave along m and n
+    constexpr int ACH = BM * (BK / 8) / NT;             // 16-byte chunks per thread, A tile
+    constexpr int BCH = BN * (BK / 8) / NT;
+    constexpr int STAGE = (BM + BN) * 8;                // chunks per stage
+    static_assert(ACH >= 1 && BCH >= 1, "tile too small for the thread count");
+    static_assert(KW == 1 || 4 * MI * NI * 16 * 64 * 4 <= 2 * STAGE * 16, "accumulator exchange must fit the LDS stages");
+    __shared__ uint4 lds[2 * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
     const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int k_begin = blockIdx.z * g.k_per_split, k_end = min(g.K, k_begin + g.k_per_split);
+    float *C = g.C + (size_t)blockIdx.z * g.c_split;
 
-    uint4 ra[ACH], rb[BCH];
-    auto load_tiles = [&](int k0) {
+    // this thread's chunks: row c >> 3, chunk c & 7 of the A tile and of the B tile.  Loads are
+    // unconditional (straight-line code keeps the ring's loads in flight across K-steps): rows past
+    // the edge are clamped to the last row (their products are never written), chunks past the end
+    // of K are clamped to the last chunk and replaced by zeros after the load.
+    const bf16_t *pa[ACH], *pb[BCH];
+    const int kc = (tid & 7) * 8;
 #pragma unroll
-        for (int i = 0; i < ACH; ++i) {
-            int c = tid + i * 256, row = c >> 3, kc = (c & 7) * 8;
-            int m = m0 + row, k = k0 + kc;
-            ra[i] = (m < g.M && k < g.K) ? *reinterpret_cast<const uint4 *>(g.A + (size_t)m * g.lda + k)
-                                         : make_uint4(0, 0, 0, 0);
-        }
+    for (int i = 0; i < ACH; ++i) {
+        int m = min(m0 + ((tid + i * NT) >> 3), g.M - 1);
+        pa[i] = g.A + (size_t)m * g.lda;
+    }
 #pragma unroll
-        for (int i = 0; i < BCH; ++i) {
-            int c = tid + i * 256, row = c >> 3, kc = (c & 7) * 8;
-            int n = n0 + row, k = k0 + kc;
-            const bf16_t *src = (n < g.n_split) ? g.B0 + (size_t)n * g.ldb : g.B1 + (size_t)(n - g.n_split) * g.ldb;
-            rb[i] = (n < g.N && k < g.K) ? *reinterpret_cast<const uint4 *>(src + k) : make_uint4(0, 0, 0, 0);
-        }
+    for (int i = 0; i < BCH; ++i) {
+        int n = min(n0 + ((tid + i * NT) >> 3), g.N - 1);
+        pb[i] = (n < g.n_split) ? g.B0 + (size_t)n * g.ldb : g.B1 + (size_t)(n - g.n_split) * g.ldb;
+    }
+    // (row * 8 + chunk) -> swizzled LDS position; row & 7 == (tid >> 3) & 7 for every i
+    const int st_off = (tid >> 3) * 8 + ((tid & 7) ^ ((tid >> (3 + kSwzShift)) & 7));
+
+    // Workgroups of different column tiles walk K from different starting steps (wrapping around), so
+    // that at any moment the chip's loads are spread over the memory channels instead of all sitting at
+    // the same offset of rows a power of two apart.  Only when the K range is whole steps.
+    const int span = k_end - k_begin;
+    const int rot = (span % BK == 0 && span >= 32 * BK) ? (blockIdx.x % 16) * BK : 0;
+
+    uint4 ring[NS][ACH + BCH];
+    auto load_tiles = [&](auto J, int k0) {
+        constexpr int j = decltype(J)::value;
+        int kk = k0 + rot;
+        if (kk >= k_end) kk -= span;
+        const int ko = min(kk + kc, g.K - 8);
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) ring[j][i] = *reinterpret_cast<const uint4 *>(pa[i] + ko);
+#pragma unroll
+        for (int i = 0; i < BCH; ++i) ring[j][ACH + i] = *reinterpret_cast<const uint4 *>(pb[i] + ko);
     };
-    auto store_tiles = [&]() {
+    // k0: the K-step the set was loaded for.  In a step that reaches past k_end the chunks of A at or
+    // past k_end become zeros (B stays as loaded: finite values times zero); this happens here, where
+    // the loaded value is needed anyway (touching it earlier would wait for the load).
+    auto store_tiles = [&](auto J, int stage, int k0) {
+        constexpr int j = decltype(J)::value;
+        uint4 *base = lds + stage * STAGE;
+        if (k0 + BK > k_end) {
+            const unsigned keep = (k0 + kc < k_end) ? 0xffffffffu : 0u;
 #pragma unroll
-        for (int i = 0; i < ACH; ++i) {
-            int c = tid + i * 256, row = c >> 3, kc = (c & 7) * 8;
-            *reinterpret_cast<uint4 *>(As + row * LDT + kc) = ra[i];
+            for (int i = 0; i < ACH; ++i) {
+                const uint4 v = ring[j][i];
+                base[st_off + i * NT] = make_uint4(v.x & keep, v.y & keep, v.z & keep, v.w & keep);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < ACH; ++i) base[st_off + i * NT] = ring[j][i];
         }
 #pragma unroll
-        for (int i = 0; i < BCH; ++i) {
-            int c = tid + i * 256, row = c >> 3, kc = (c & 7) * 8;
-            *reinterpret_cast<uint4 *>(Bs + row * LDT + kc) = rb[i];
-        }
+        for (int i = 0; i < BCH; ++i) base[BM * 8 + st_off + i * NT] = ring[j][ACH + i];
     };
 
     f32x16 acc[MI][NI];
@@ -139,28 +196,77 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_nt(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    load_tiles(0);
-    for (int k0 = 0; k0 < g.K; k0 += BK) {
-        store_tiles();
-        __syncthreads();
-        if (k0 + BK < g.K) load_tiles(k0 + BK);
-        const int fr = lane & 31, fk = (lane >> 5) * 8;
+    const int fr = lane & 31, hb = lane >> 5, sw = (fr >> kSwzShift) & 7;
+    const int a_row = (wm * (BM / 2) + fr) * 8, b_row = (BM + wn * (BN / 2) + fr) * 8;
+
+    // multiplies the K-step at k0 = step t, with J = (t + 1) % NS: set J - 1 (step t, already in LDS) is
+    // free and takes step t + NS; set J (step t + 1) goes to LDS afterwards
+    auto step = [&](auto J, int k0) {
+        constexpr int j = decltype(J)::value;
+        constexpr int stage = j & 1;
+        load_tiles(std::integral_constant<int, (j + NS - 1) % NS>{}, k0 + NS * BK);
+        const uint4 *base = lds + stage * STAGE;
 #pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
+        for (int s0 = 0; s0 < BK / 16 / KW; ++s0) {
             bf16x8 fa[MI], fb[NI];
+            const int s = kh * (BK / 16 / KW) + s0;
+            const int ch = (2 * s + hb) ^ sw;
 #pragma unroll
-            for (int a = 0; a < MI; ++a)
-                fa[a] = *reinterpret_cast<const bf16x8 *>(As + (wm * (BM / 2) + a * 32 + fr) * LDT + s * 16 + fk);
+            for (int a = 0; a < MI; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(base + a_row + a * 32 * 8 + ch);
 #pragma unroll
-            for (int b = 0; b < NI; ++b)
-                fb[b] = *reinterpret_cast<const bf16x8 *>(Bs + (wn * (BN / 2) + b * 32 + fr) * LDT + s * 16 + fk);
+            for (int b = 0; b < NI; ++b) fb[b] = *reinterpret_cast<const bf16x8 *>(base + b_row + b * 32 * 8 + ch);
 #pragma unroll
             for (int a = 0; a < MI; ++a)
 #pragma unroll
                 for (int b = 0; b < NI; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
+        store_tiles(J, stage ^ 1, k0 + BK);   // the other stage was last read before the previous barrier
         __syncthreads();
+    };
+
+    // sets 0 .. NS-1 <- steps 0 .. NS-1, step 0 on to LDS stage 1
+    static_assert(NS % 2 == 0, "LDS stage parity follows the ring index");
+    auto prologue = [&](auto self, auto I) {
+        constexpr int i = decltype(I)::value;
+        if constexpr (i < NS) {
+            load_tiles(I, k_begin + i * BK);
+            self(self, std::integral_constant<int, i + 1>{});
+        }
+    };
+    prologue(prologue, std::integral_constant<int, 0>{});
+    store_tiles(std::integral_constant<int, 0>{}, 1, k_begin);
+    __syncthreads();
+    // always whole rounds of NS steps (no exits inside the round: straight-line code keeps the waits on
+    // the ring exact); steps past k_end multiply zeros
+    auto round = [&](auto self, auto I, int k0) {
+        constexpr int i = decltype(I)::value;
+        if constexpr (i < NS) {
+            step(std::integral_constant<int, (i + 1) % NS>{}, k0 + i * BK);
+            self(self, std::integral_constant<int, i + 1>{}, k0);
+        }
+    };
+    for (int k0 = k_begin; k0 < k_end; k0 += NS * BK) round(round, std::integral_constant<int, 0>{}, k0);
+
+    if constexpr (KW == 2) {
+        // the loop ended with a barrier: the stages are free
+        float *xf = reinterpret_cast<float *>(lds);
+        if (kh == 1) {
+#pragma unroll
+            for (int a = 0; a < MI; ++a)
+#pragma unroll
+                for (int b = 0; b < NI; ++b)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) xf[(((wave * MI + a) * NI + b) * 16 + r) * 64 + lane] = acc[a][b][r];
+        }
+        __syncthreads();
+        if (kh == 1) return;
+#pragma unroll
+        for (int a = 0; a < MI; ++a)
+#pragma unroll
+            for (int b = 0; b < NI; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][b][r] += xf[(((wave * MI + a) * NI + b) * 16 + r) * 64 + lane];
     }
 
     // accumulator register r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of its 32x32 tile
@@ -172,7 +278,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_nt(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < g.M && col < g.N) g.C[(size_t)row * g.ldc + col] = acc[a][b][r];
+                if (row < g.M && col < g.N) C[(size_t)row * g.ldc + col] = acc[a][b][r];
             }
         }
 }
@@ -180,17 +286,32 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_nt(GemmArgs g)
 // ---------------------------------------------------------------------------
 // Rotary embedding + cache fill from the fp32 QKV product
 // ---------------------------------------------------------------------------
-// One thread per (token, pair index e): rotates element pair (e, e + d/2) of every query and key head at
-// position pos0 + token (angle in fp64), writes q as bf16 [n][nq*d], K and V into cache slot pos0 + token.
-__global__ __launch_bounds__(256) void k_rope_scatter(const float *__restrict__ qkv, bf16_t *__restrict__ q_out,
-                                                      bf16_t *__restrict__ Kc, bf16_t *__restrict__ Vc, int n, int nq,
-                                                      int nkv, int d, int max_seq, int pos0, double log2_base)
+// One thread per (token, head slot, pair index e); head slots are the nq query heads, the nkv key heads and
+// the nkv value heads.  Query and key slots rotate element pair (e, e + d/2) at position pos0 + token (angle
+// in fp64); q goes out as bf16 [n][nq*d], K and V into cache slot pos0 + token.
+// The QKV product arrives as n_parts split-K partials, part_stride floats apart, added in split order.
+__global__ __launch_bounds__(256) void k_rope_scatter(const float *__restrict__ qkv, int n_parts, size_t part_stride,
+                                                      bf16_t *__restrict__ q_out, bf16_t *__restrict__ Kc,
+                                                      bf16_t *__restrict__ Vc, int n, int nq, int nkv, int d,
+                                                      int max_seq, int pos0, double log2_base)
 {
-    const int half = d / 2;
+    const int half = d / 2, nh = nq + 2 * nkv;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n * half) return;
-    const int t = idx / half, e = idx - t * half;
+    if (idx >= n * nh * half) return;
+    const int e = idx % half, hs = (idx / half) % nh, t = idx / (half * nh);
     const int pos = pos0 + t;
+    const float *row0 = qkv + (size_t)t * nh * d + (size_t)hs * d;
+    float lo = row0[e], hi = row0[e + half];
+    for (int p = 1; p < n_parts; ++p) {
+        lo += row0[(size_t)p * part_stride + e];
+        hi += row0[(size_t)p * part_stride + e + half];
+    }
+    if (hs >= nq + nkv) {
+        const size_t slot = ((size_t)(hs - nq - nkv) * max_seq + pos) * d;
+        Vc[slot + e] = f32_to_bf16(lo);
+        Vc[slot + e + half] = f32_to_bf16(hi);
+        return;
+    }
     float cs = 1.f, sn = 0.f;
     if (pos != 0) {
         double theta = exp2(-(2.0 * (double)e / (double)d) * log2_base);
@@ -199,20 +320,14 @@ __global__ __launch_bounds__(256) void k_rope_scatter(const float *__restrict__ 
         cs = (float)cd;
         sn = (float)sd;
     }
-    const int ld = (nq + 2 * nkv) * d;
-    const float *row = qkv + (size_t)t * ld;
-    for (int hd = 0; hd < nq; ++hd) {
-        float lo = row[hd * d + e], hi = row[hd * d + e + half];
-        q_out[(size_t)t * nq * d + hd * d + e] = f32_to_bf16(lo * cs - hi * sn);
-        q_out[(size_t)t * nq * d + hd * d + e + half] = f32_to_bf16(hi * cs + lo * sn);
-    }
-    for (int gk = 0; gk < nkv; ++gk) {
-        float lo = row[(nq + gk) * d + e], hi = row[(nq + gk) * d + e + half];
-        size_t slot = ((size_t)gk * max_seq + pos) * d;
-        Kc[slot + e] = f32_to_bf16(lo * cs - hi * sn);
-        Kc[slot + e + half] = f32_to_bf16(hi * cs + lo * sn);
-        Vc[slot + e] = f32_to_bf16(row[(nq + nkv + gk) * d + e]);
-        Vc[slot + e + half] = f32_to_bf16(row[(nq + nkv + gk) * d + e + half]);
+    const bf16_t rlo = f32_to_bf16(lo * cs - hi * sn), rhi = f32_to_bf16(hi * cs + lo * sn);
+    if (hs < nq) {
+        q_out[((size_t)t * nq + hs) * d + e] = rlo;
+        q_out[((size_t)t * nq + hs) * d + e + half] = rhi;
+    } else {
+        const size_t slot = ((size_t)(hs - nq) * max_seq + pos) * d;
+        Kc[slot + e] = rlo;
+        Kc[slot + e + half] = rhi;
     }
 }
 
@@ -336,40 +451,42 @@ __global__ __launch_bounds__(256) void k_prefill_attn(const bf16_t *__restrict__
 // Causal GQA attention on the matrix cores (head_dim a multiple of 32, at most 128)
 // ---------------------------------------------------------------------------
 // Rows are the (token, query head of the group) pairs of one KV head, row = token * G + head.
-// A wave owns 32 rows and walks the key tiles (32 slots) its rows may see; the four waves of a
-// workgroup own consecutive row tiles and share the V tile through LDS.
+// A workgroup owns 32 rows; its four waves share them and split the key tiles (32 slots each,
+// tile t goes to wave t % 4), each with a running softmax of its own, merged through LDS at the end.
 //
 // Scores are formed transposed, S^T[key][row] = K . Q^T: both operands are then read along the
 // head dimension, straight from global memory, and a lane ends up with 16 scores of ONE row
 // (its column), so the running softmax is in-lane work plus one exchange between the two
 // half-waves.  O^T[e][row] += V^T[e][key] . P^T[key][row]: P^T is exactly the score registers
-// (cast to bf16), no data movement; V^T is read from an LDS tile laid out [key / 4][e][key % 4],
-// in the key order the score registers hold (the contraction index may be permuted as long as
-// both operands agree).
+// (cast to bf16), no data movement; V^T is read from a per-wave LDS tile laid out
+// [key / 4][e][key % 4], in the key order the score registers hold (the contraction index may be
+// permuted as long as both operands agree).
 template <int D>
 __global__ __launch_bounds__(256) void k_prefill_attn_mfma(const bf16_t *__restrict__ q, const bf16_t *__restrict__ Kc,
                                                            const bf16_t *__restrict__ Vc, bf16_t *__restrict__ o, int n,
                                                            int nq, int nkv, int max_seq, int pos0)
 {
     constexpr int ET = D / 32, KS = D / 16, TK = 32;
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[(TK / 4) * D * 4];
+    constexpr int VT = (TK / 4) * D * 4;                          // bf16 elements of one V tile
+    constexpr int MERGE = 3 * ET * 16 * 64;                       // floats: three foreign shares of every output tile
+    constexpr int LDS_BYTES = (4 * VT * 2 > MERGE * 4) ? 4 * VT * 2 : MERGE * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
+    __shared__ float ml[2][4][32];                                // running max and sum of every wave's rows
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hb = lane >> 5;
     const int G = nq / nkv, gk = blockIdx.y;
     const int n_rows = n * G;
-    const int row = (blockIdx.x * 4 + wave) * 32 + col;          // this lane's row (a column of S^T)
+    const int row = blockIdx.x * 32 + col;                        // this lane's row (a column of S^T)
     const bool row_ok = row < n_rows;
     const int tok = row_ok ? row / G : n - 1, head = gk * G + (row_ok ? row % G : 0);
     const int my_last = pos0 + tok;                               // last slot this row attends to
-    const int wave_first_row = (blockIdx.x * 4 + wave) * 32;
-    const int wave_last_tok = min(n - 1, (wave_first_row + 31) / G);
-    const int wg_last_tok = min(n - 1, ((blockIdx.x * 4 + 3) * 32 + 31) / G);
-    const bool wave_ok = wave_first_row < n_rows;
-    const int wave_last_key = pos0 + wave_last_tok, wg_last_key = pos0 + wg_last_tok;
+    const int wg_last_key = pos0 + min(n - 1, (blockIdx.x * 32 + 31) / G);
     const float scale = 1.0f / sqrtf((float)D);
     const bf16_t *Kg = Kc + (size_t)gk * max_seq * D;
     const bf16_t *Vg = Vc + (size_t)gk * max_seq * D;
+    bf16_t *Vt = reinterpret_cast<bf16_t *>(smem) + wave * VT;
+    TPI_PTRACE(blockIdx.x, 0);
 
     bf16x8 qf[KS];
     {
@@ -384,33 +501,56 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(const bf16_t *__restr
         for (int r = 0; r < 16; ++r) oacc[et][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    for (int k0 = 0; k0 <= wg_last_key; k0 += TK) {
-        __syncthreads();
-        // V tile -> LDS, transposed into [key / 4][e][key % 4]
-        for (int c = tid; c < TK * (D / 8); c += 256) {
-            int key = c / (D / 8), e0 = (c - key * (D / 8)) * 8;
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (k0 + key <= wg_last_key) raw = *reinterpret_cast<const uint4 *>(Vg + (size_t)(k0 + key) * D + e0);
-            const bf16_t *ev = reinterpret_cast<const bf16_t *>(&raw);
+    // Loads of one key tile, always in bounds (slots past the workgroup's last key are clamped to it; their
+    // probabilities are zero).  K: the lane's MFMA fragments, rows of the MFMA = keys k0 .. k0+31.  V: lane =
+    // output element e (EP passes of 64), one 16-bit load per key, coalesced across the wave, packed in
+    // pairs of keys: what the lane then writes to LDS is already transposed.
+    constexpr int EP = (D + 63) / 64;
+    bf16x8 kf_next[KS];
+    unsigned v_next[EP][TK];      // raw 16-bit loads; packed only where they are stored (no use next to the loads)
+    auto fetch = [&](int k0) {
+        const int key = min(k0 + col, wg_last_key);
+        const bf16_t *kp = Kg + (size_t)key * D + hb * 8;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) Vt[((key >> 2) * D + e0 + i) * 4 + (key & 3)] = ev[i];
+        for (int ks = 0; ks < KS; ++ks) kf_next[ks] = *reinterpret_cast<const bf16x8 *>(kp + ks * 16);
+#pragma unroll
+        for (int ep = 0; ep < EP; ++ep) {
+            const int e = min(ep * 64 + lane, D - 1);
+#pragma unroll
+            for (int j = 0; j < TK; ++j) v_next[ep][j] = Vg[(size_t)min(k0 + j, wg_last_key) * D + e];
         }
-        __syncthreads();
-        if (!wave_ok || k0 > wave_last_key) continue;
+    };
+    if (wave * TK <= wg_last_key) fetch(wave * TK);
+    TPI_PTRACE(blockIdx.x, 1);
 
-        // S^T tile: rows of the MFMA = keys k0 .. k0+31, columns = this wave's 32 rows
+    for (int k0 = wave * TK; k0 <= wg_last_key; k0 += 4 * TK) {
+        bf16x8 kf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kf[ks] = kf_next[ks];
+        // V tile -> this wave's LDS tile [key / 4][e][key % 4].  Only this wave touches the tile and a wave's
+        // LDS operations complete in order, so no workgroup barrier is needed around it.
+#pragma unroll
+        for (int ep = 0; ep < EP; ++ep) {
+            const int e = ep * 64 + lane;
+            if (e < D) {
+#pragma unroll
+                for (int kg = 0; kg < TK / 4; ++kg)
+                    *reinterpret_cast<uint2 *>(Vt + (kg * D + e) * 4) =
+                        make_uint2(v_next[ep][4 * kg] | (v_next[ep][4 * kg + 1] << 16),
+                                   v_next[ep][4 * kg + 2] | (v_next[ep][4 * kg + 3] << 16));
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        fetch(min(k0 + 4 * TK, wg_last_key));                     // next round's tile, in flight during this one
+        if (k0 == 0) TPI_PTRACE(blockIdx.x, 2);
+
         f32x16 sacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-        {
-            const int key = min(k0 + col, wg_last_key);           // clamped: masked below
-            const bf16_t *kp = Kg + (size_t)key * D + hb * 8;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kp + ks * 16);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
-            }
-        }
+        for (int ks = 0; ks < KS; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
         // register r of this lane: key k0 + 8*(r/4) + 4*hb + r%4, row = this lane's column
         float mt = -INFINITY;
 #pragma unroll
@@ -432,7 +572,7 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(const bf16_t *__restr
         ls += __shfl_xor(ls, 32, 64);
         const float alpha = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
         l_run = l_run * alpha + ls;
-        if (m_new != -INFINITY) m_run = m_new;
+        m_run = m_new;
 #pragma unroll
         for (int et = 0; et < ET; ++et)
 #pragma unroll
@@ -458,22 +598,60 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(const bf16_t *__restr
                 oacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[s2], oacc[et], 0, 0, 0);
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the tile is rewritten by the next round
+        __builtin_amdgcn_wave_barrier();
     }
 
-    if (row_ok) {
-        const float inv = 1.0f / l_run;
-        bf16_t *op = o + ((size_t)tok * nq + head) * D;
+    TPI_PTRACE(blockIdx.x, 3);
+    // merge the four waves: common maximum, rescale, waves 1..3 hand their partial outputs to wave 0
+    if (hb == 0) { ml[0][wave][col] = m_run; ml[1][wave][col] = l_run; }
+    __syncthreads();                                              // also: every wave is done with its V tile
+    float m_all = fmaxf(fmaxf(ml[0][0][col], ml[0][1][col]), fmaxf(ml[0][2][col], ml[0][3][col]));
+    float l_all = 0.f;
 #pragma unroll
-        for (int et = 0; et < ET; ++et)
+    for (int w = 0; w < 4; ++w) {
+        float mw = ml[0][w][col];
+        l_all += (mw == -INFINITY) ? 0.f : ml[1][w][col] * __expf(mw - m_all);
+    }
+    const float mine = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_all);
+    // output tile et (32 elements of every row) is finished by wave et: the other three waves hand it their
+    // share through LDS, slot [et][p], p = the source wave's rank among the waves other than et
+    float *mg = reinterpret_cast<float *>(smem);
+    TPI_PTRACE(blockIdx.x, 4);
+#pragma unroll
+    for (int et = 0; et < ET; ++et) {
+        if (wave != et) {
+            const int pslot = et * 3 + (wave < et ? wave : wave - 1);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mg[(pslot * 16 + r) * 64 + lane] = oacc[et][r] * mine;
+        }
+    }
+    __syncthreads();
+    TPI_PTRACE(blockIdx.x, 5);
+#pragma unroll
+    for (int et = 0; et < ET; ++et) {
+        if (wave == et && row_ok) {
+            const float inv = 1.0f / l_all;
+            bf16_t *op = o + ((size_t)tok * nq + head) * D;
+            float part[3][16];
+#pragma unroll
+            for (int w = 0; w < 3; ++w)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) part[w][r] = mg[((et * 3 + w) * 16 + r) * 64 + lane];
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
                 // registers 4*r4 .. 4*r4+3: elements e = 32*et + 8*r4 + 4*hb + 0..3
                 union { uint2 v; bf16_t u[4]; } pk;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pk.u[i] = f32_to_bf16(oacc[et][4 * r4 + i] * inv);
+                for (int i = 0; i < 4; ++i) {
+                    const int r = 4 * r4 + i;
+                    pk.u[i] = f32_to_bf16((oacc[et][r] * mine + part[0][r] + part[1][r] + part[2][r]) * inv);
+                }
                 *reinterpret_cast<uint2 *>(op + 32 * et + 8 * r4 + 4 * hb) = pk.v;
             }
+        }
     }
+    TPI_PTRACE(blockIdx.x, 6);
 }
 
 // ---------------------------------------------------------------------------
@@ -487,13 +665,48 @@ struct PrefillLayout {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Tile shape and K split of one GEMM.  128x128 tiles once there are more than 64 rows; when the
+// tiles alone leave most of the 256 compute units idle, smaller tiles, or (where the caller has
+// room for partial products) a split along K.
+struct GemmPlan {
+    int bm, bn, splits, k_per_split;
+};
+
+constexpr int kMaxGemmSplits = 8;
+
+GemmPlan plan_gemm(int M, int N, int K, int max_splits)
+{
+    GemmPlan p{128, 128, 1, cdiv(K, 64) * 64};
+    if (M <= 64) p.bm = 64;
+    int tiles = cdiv(M, p.bm) * cdiv(N, p.bn);
+    if (tiles < 128 && max_splits > 1) {
+        const int ksteps = cdiv(K, 64);
+        int want = std::min(std::min(max_splits, 256 / tiles), std::max(1, ksteps / 4));
+        if (want > 1) {
+            const int per = cdiv(ksteps, want);
+            p.splits = cdiv(ksteps, per);
+            p.k_per_split = per * 64;
+            return p;
+        }
+    }
+    if (tiles < 128 && p.bm == 128) {
+        p.bm = 64;
+        tiles = cdiv(M, 64) * cdiv(N, 128);
+    }
+    if (tiles < 128) p.bn = 64;
+    return p;
+}
+
 PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
 {
     PrefillLayout L;
     const size_t dq = (size_t)c->n_q_local * c->head_dim, dkv = (size_t)c->n_kv_local * c->head_dim;
     size_t off = 0;
     L.xn = off;  off += align256((size_t)n * c->hidden * 2);
-    size_t qkv = (size_t)n * (dq + 2 * dkv) * 4, gu = (size_t)n * 2 * c->ffn_local * 4;
+    const GemmPlan pq = plan_gemm(n, (int)(dq + 2 * dkv), c->hidden, kMaxGemmSplits);
+    size_t qkv = (size_t)pq.splits * n * (dq + 2 * dkv) * 4, gu = (size_t)n * 2 * c->ffn_local * 4;
     L.big = off; off += align256(qkv > gu ? qkv : gu);
     L.q = off;   off += align256((size_t)n * dq * 2);
     L.o = off;   off += align256((size_t)n * dq * 2);
@@ -502,20 +715,19 @@ PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
     return L;
 }
 
+// max_splits > 1: C must have room for that many partial products of M * ldc floats; the number
+// actually written is returned in *n_parts.
 hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t *B1, int n_split, int ldb, float *C,
-                       int ldc, int M, int N, int K, hipStream_t st)
+                       int ldc, int M, int N, int K, hipStream_t st, int max_splits = 1, int *n_parts = nullptr)
 {
-    GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc};
+    const GemmPlan p = plan_gemm(M, N, K, max_splits);
+    if (n_parts) *n_parts = p.splits;
+    GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc, p.k_per_split, (size_t)M * ldc};
     ProfScope ps(kStagePrefillGemm, st);
-    // full 128x128 tiles when they alone fill the chip twice over, else smaller tiles for more workgroups
-    const long big_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
-    if (big_tiles >= 512) {
-        hipLaunchKernelGGL((k_gemm_bf16_nt<128, 128>), dim3((N + 127) / 128, (M + 127) / 128), dim3(256), 0, st, g);
-    } else if ((long)((M + 63) / 64) * ((N + 127) / 128) >= 256) {
-        hipLaunchKernelGGL((k_gemm_bf16_nt<64, 128>), dim3((N + 127) / 128, (M + 63) / 64), dim3(256), 0, st, g);
-    } else {
-        hipLaunchKernelGGL((k_gemm_bf16_nt<64, 64>), dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, g);
-    }
+    dim3 grid(cdiv(N, p.bn), cdiv(M, p.bm), p.splits);
+    if (p.bm == 128) hipLaunchKernelGGL((k_gemm_bf16_nt<128, 128, 4, 2>), grid, dim3(512), 0, st, g);
+    else if (p.bn == 128) hipLaunchKernelGGL((k_gemm_bf16_nt<64, 128, 4, 1>), grid, dim3(256), 0, st, g);
+    else hipLaunchKernelGGL((k_gemm_bf16_nt<64, 64, 4, 1>), grid, dim3(256), 0, st, g);
     return hipGetLastError();
 }
 
@@ -554,15 +766,17 @@ int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi
         hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n), dim3(256), 0, st, (const bf16_t *)h_in, (const float *)w->attn_norm,
                            xn, h, c->rms_eps);
         TPI_LAUNCH_OK();
+        int qkv_parts = 1;
         e = launch_gemm(xn, h, (const bf16_t *)w->w_qkv, (const bf16_t *)w->w_qkv, dq + 2 * dkv, h, big, dq + 2 * dkv, n,
-                        dq + 2 * dkv, h, st);
+                        dq + 2 * dkv, h, st, kMaxGemmSplits, &qkv_parts);
         if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
-        const int nthr = n * (d / 2);
-        hipLaunchKernelGGL(k_rope_scatter, dim3((nthr + 255) / 256), dim3(256), 0, st, big, qb, (bf16_t *)kv->k,
+        const int nthr = n * (nq + 2 * nkv) * (d / 2);
+        hipLaunchKernelGGL(k_rope_scatter, dim3((nthr + 255) / 256), dim3(256), 0, st, big, qkv_parts,
+                           (size_t)n * (dq + 2 * dkv), qb, (bf16_t *)kv->k,
                            (bf16_t *)kv->v, n, nq, nkv, d, c->max_seq, pos0, std::log2((double)c->rope_base));
         TPI_LAUNCH_OK();
         if (d % 32 == 0 && d <= 128) {
-            dim3 grid((n * G + 127) / 128, nkv);
+            dim3 grid((n * G + 31) / 32, nkv);
             switch (d) {
             case 32: hipLaunchKernelGGL((k_prefill_attn_mfma<32>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
             case 64: hipLaunchKernelGGL((k_prefill_attn_mfma<64>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
@@ -617,3 +831,10 @@ int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi
 }
 
 }  // namespace tpi
+
+#ifdef TPI_TRACE
+extern "C" int tpi_debug_read_ptrace(unsigned long long *host_out, int n)
+{
+    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(tpi::g_ptrace), sizeof(unsigned long long) * n) == hipSuccess ? 0 : -3;
+}
+#endif
