@@ -268,6 +268,21 @@ def prefill_leg(args, m, L, N, seed):
     }
 
 
+# HBM bytes of one k_gate_up launch as the byte counters saw them (rocprofv3 --pmc FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch, each scaled by 2.0: the factor by which the same counters under-read a plain
+# 1 GiB device copy).  A figure from separate profiler runs of this command, kept in profiles/; None for a
+# workload those runs did not cover.
+MEASURED_GATE_UP_TRAFFIC = {
+    ("llama2-70b-shaped-tp8", 8): {"bytes": round((918724.6 + 451.1) * 2.0 * 1024),
+                                   "source": "profiles/decode_70b_tp8_eight_shards_per_launch.md"},
+}
+
+
+def measured_traffic(m, n_launch_shards):
+    hit = MEASURED_GATE_UP_TRAFFIC.get((m.name, n_launch_shards))
+    return hit["bytes"] if hit else None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -514,7 +529,7 @@ def main():
                       "ms_per_token_reduce_folded_into_phase": round(fused_ms, 4) if fused_ms else None},
         "roofline": {"kernel": f"k_gate_up (RMSNorm + gate/up GEMV + SiLU gate, {n_launch_shards} shard(s) per launch)",
                      "bound": "hbm", "achieved": round(gu_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(m, n_launch_shards),
                      "bytes_per_launch": gu_bytes, "avg_launch_us": round(gu_avg_ms * 1e3, 2), "launches": gu_n},
         "output_finite": finite,
         "setup_s": round(setup_s, 1),

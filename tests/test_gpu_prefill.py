@@ -46,6 +46,7 @@ def _run_prefill_case(h, nq, nkv, d, sl, n, pos0, max_seq, seed, attn_scale=1.0)
     Ko, Vo = K.copy(), V.copy()
     ref_attn = O.attn_block(oc, wb["attn_norm"], wb["w_qkv"], wb["w_o"], Ko, Vo, pos0, x)
     e = rel_err(got_attn, ref_attn)
+    print(f"prefill h={h} nq={nq} nkv={nkv} d={d} n={n} pos0={pos0}: attention partial rel err {e:.2e}", flush=True)
     assert e <= BF16_TOL, f"attention partial rel err {e:.3e}"
     Kg, Vg = Kt.float().cpu().numpy(), Vt.float().cpu().numpy()
     for garr, before, after in ((Kg, K, Ko), (Vg, V, Vo)):
@@ -58,6 +59,7 @@ def _run_prefill_case(h, nq, nkv, d, sl, n, pos0, max_seq, seed, attn_scale=1.0)
     torch.cuda.synchronize()
     ref_ffn = O.ffn_block(oc, wb["ffn_norm"], wb["w_gate"], wb["w_up"], wb["w_down"], x)
     e = rel_err(part.cpu().numpy(), ref_ffn)
+    print(f"prefill h={h} sl={sl} n={n}: FFN partial rel err {e:.2e}", flush=True)
     assert e <= BF16_TOL, f"FFN partial rel err {e:.3e}"
     return got_attn, ref_attn
 
