@@ -51,6 +51,10 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true", help="skip the bf16 prefill leg")
     ap.add_argument("--prefill-tokens", type=int, default=512)
     ap.add_argument("--prefill-steps", type=int, default=3)
+    ap.add_argument("--no-window-prefill", action="store_true",
+                    help="skip the windowed long-prompt prefill (the point where the copies can hide)")
+    ap.add_argument("--window-prefill-tokens", type=int, default=16384)
+    ap.add_argument("--window-prefill-layers", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
     ap.add_argument("--seed", type=int, default=0)
@@ -175,6 +179,130 @@ def window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_
         "copy_ms_per_token_at_link_peak": round(copy_ms, 2), "resident_ms_per_token": round(ms_resident, 3),
         "hidden_fraction": round(1.0 - (ms - ms_resident) / copy_ms, 4),
         "compute_over_copy": round(ms_resident / copy_ms, 4), "output_finite": finite,
+    }
+
+
+def window_prefill_leg(args, m, seed):
+    """The favourable point of the sliding window: one shard's bf16 layer blobs stream from pinned host
+    memory through --window-layers HBM slots while a LONG prompt is prefilled.  Per layer the shard then
+    computes for longer than its blob takes to copy (the loose steady condition of the paper's Prop. 3
+    holds), so the copies should disappear behind the compute; with batch-1 decode they cannot."""
+    import torch
+
+    from paper_2410_00531_amd import binding as B
+    from paper_2410_00531_amd import synth
+    dev = torch.device("cuda:0")
+    n, L, Wn, D = args.window_prefill_tokens, args.window_prefill_layers, args.window_layers, 8
+    Wn = min(Wn, L)
+    h, d, sl, nq, nkv = m.hidden, m.head_dim, m.ffn_local, m.nq_local, m.nkv_local
+    cfg = B.make_cfg(h, nq, nkv, d, sl, n, m.rms_eps, m.rope_base, dtype=B.TPI_BF16)
+    layout, nbytes = synth.blob_layout_bytes(h, nq, nkv, d, sl, 2)
+    gen = torch.Generator(device=dev); gen.manual_seed(seed + 9)
+    dev_blobs, host = [], []
+    for i in range(min(D, L)):                      # D distinct blobs; layer l uses blob l % D (same traffic)
+        b = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        for name, (off, shape, item) in layout.items():
+            cnt = 1
+            for s_ in shape:
+                cnt *= s_
+            if item == 4:
+                b[off:off + cnt * 4].view(torch.float32).normal_(1.0, 0.02, generator=gen)
+            else:
+                b[off:off + cnt * 2].view(torch.bfloat16).normal_(0.0, 0.02, generator=gen)
+        hb = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        hb.copy_(b)
+        dev_blobs.append(b); host.append(hb)
+    D = len(dev_blobs)
+    slots = torch.empty(Wn * nbytes, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def link_peak():
+        """Practical peak of the link: plain pinned copies of whole blobs, best of several rounds (measured
+        right after earlier phases released their memory the first rounds have read about half)."""
+        best = 0.0
+        for _ in range(6):
+            e0.record()
+            for i in range(D):
+                slots[:nbytes].copy_(host[i], non_blocking=True)
+            e1.record(); torch.cuda.synchronize()
+            best = max(best, D * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        return best
+
+    def views(base):
+        w = (B.tpi_layer_weights * 1)()
+        for name, (off, _, _) in layout.items():
+            setattr(w[0], name, base + off)
+        return w
+
+    res_w = [views(b.data_ptr()) for b in dev_blobs]
+    slot_w = {slots.data_ptr() + i * nbytes: views(slots.data_ptr() + i * nbytes) for i in range(Wn)}
+    x32 = torch.randn((n, h), generator=gen, device=dev)
+    x16 = x32.to(torch.bfloat16)
+    ha32 = torch.empty_like(x32); ha16 = torch.empty_like(x16)
+    hb32 = torch.empty_like(x32); hb16 = torch.empty_like(x16)
+    part = torch.empty((n, h), dtype=torch.float32, device=dev)
+    others = torch.zeros((n, h), dtype=torch.float32, device=dev)     # the other ranks' partials (read only)
+    N = m.n_shards
+    P = (C.c_void_p * N)(part.data_ptr(), *[others.data_ptr()] * (N - 1))
+    kc = torch.zeros((L, 2, nkv, n, d), dtype=torch.bfloat16, device=dev)
+    KV = [B.make_kv(kc[l, 0], kc[l, 1]) for l in range(L)]
+    ws = torch.empty(B.tpi_workspace_bytes(cfg, n) // 4, dtype=torch.float32, device=dev)
+    lib = B.lib(); stream = torch.cuda.current_stream().cuda_stream; cfg_p = C.byref(cfg)
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(B.tpi_last_error())
+
+    def prompt(get_layer, release_layer):
+        s32, s16 = x32, x16
+        for l in range(L):
+            w = get_layer(l)
+            check(lib.tpi_shard_layer_prefill(cfg_p, w, C.byref(KV[l]), 0, n, B.TPI_PHASE_ATTN, s16.data_ptr(),
+                                              part.data_ptr(), ws.data_ptr(), stream))
+            check(lib.tpi_star_reduce_bf16(P, N, n * h, s32.data_ptr(), ha32.data_ptr(), ha16.data_ptr(), stream))
+            check(lib.tpi_shard_layer_prefill(cfg_p, w, None, 0, n, B.TPI_PHASE_FFN, ha16.data_ptr(),
+                                              part.data_ptr(), ws.data_ptr(), stream))
+            check(lib.tpi_star_reduce_bf16(P, N, n * h, ha32.data_ptr(), hb32.data_ptr(), hb16.data_ptr(), stream))
+            release_layer(l)
+            s32, s16 = hb32, hb16
+        return s32
+
+    def timed(fn, reps):
+        fn(); torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            out = fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / reps, out
+
+    ms_res, out_res = timed(lambda: prompt(lambda l: res_w[l % D], lambda l: None), 2)
+    ref = out_res.clone()
+    link_gbps = link_peak()
+    win = B.Window([host[l % D] for l in range(L)], slots, Wn, nbytes)
+    for l in range(Wn):
+        win.prefetch(l)
+    nxt = [Wn]
+
+    def release_layer(l):
+        win.release(l)
+        win.prefetch(nxt[0] % L)                  # slides on into the next prompt's layers
+        nxt[0] += 1
+
+    ms_win, out_win = timed(lambda: prompt(lambda l: slot_w[win.acquire(l)], release_layer), 2)
+    same = bool(torch.equal(out_win, ref))
+    win_copy_ms, win_copy_bytes = win.copy_stats()
+    win.destroy()
+    copy_ms = L * nbytes / (link_gbps * 1e9) * 1e3
+    return {
+        "workload": f"{m.name}-windowed-prefill-{n}-tokens-one-shard", "dtype": "bf16 weights, fp32 partials",
+        "layers": L, "window_layers": Wn, "layer_blob_mb": round(nbytes / 1e6, 2),
+        "ms_per_prompt_windowed": round(ms_win, 2), "ms_per_prompt_resident": round(ms_res, 2),
+        "copy_ms_per_prompt_at_link_peak": round(copy_ms, 2), "link_peak_gbps_plain_copy": round(link_gbps, 2),
+        "compute_over_copy": round(ms_res / copy_ms, 3),
+        "hidden_fraction": round(min(1.0, 1.0 - (ms_win - ms_res) / copy_ms), 4),
+        "copy_stream_effective_gbps": round(win_copy_bytes / (win_copy_ms * 1e-3) / 1e9, 2) if win_copy_ms > 0 else None,
+        "windowed_equals_resident_bitwise": same,
     }
 
 
@@ -571,10 +699,17 @@ def main():
                       f"workload's shape, {per_layer_shard_ms:.2f} ms each, scaled x{L} layers x{N} shards",
         }
     # ---- bf16 prefill of the same stack (the fp32 stack is released first: both do not fit) -------
-    if not args.no_prefill and args.mode == "both":
+    want_prefill = not args.no_prefill and args.mode == "both"
+    want_window_prefill = not args.no_window and not args.no_window_prefill and args.mode == "both"
+    if want_prefill or want_window_prefill:
         del blobs, kc, W_all, KV_all, W_one, KV_one
         torch.cuda.empty_cache()
+    if want_prefill:
         result["prefill"] = prefill_leg(args, m, L, N, args.seed)
+        torch.cuda.empty_cache()
+    # ---- the window where PCIe allows hiding: a long prompt through one shard's windowed layers ---
+    if want_window_prefill:
+        result.setdefault("window", {})["long_prompt_prefill"] = window_prefill_leg(args, m, args.seed)
     print(json.dumps(result))
 
 

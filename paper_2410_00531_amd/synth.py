@@ -75,3 +75,17 @@ def to_bf16_grid(x: np.ndarray) -> np.ndarray:
     u = np.ascontiguousarray(x, np.float32).view(np.uint32)
     rounded = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
     return rounded.view(np.float32)
+
+
+def blob_layout_bytes(hidden, nq, nkv, d, ffn_local, matrix_itemsize):
+    """Byte layout of one contiguous layer-shard blob: the tensors of TENSOR_ORDER, each starting on a
+    256-byte boundary; norm gains are fp32, matrices have `matrix_itemsize` bytes per element (4: fp32
+    decode weights, 2: bf16 prefill weights).  Returns ({name: (byte_offset, shape, itemsize)}, total_bytes)."""
+    shapes = shard_tensor_shapes(hidden, nq, nkv, d, ffn_local)
+    off, out = 0, {}
+    for name in TENSOR_ORDER:
+        item = 4 if name.endswith("_norm") else matrix_itemsize
+        out[name] = (off, shapes[name], item)
+        off += (int(np.prod(shapes[name])) * item + 255) // 256 * 256
+    return out, off
+

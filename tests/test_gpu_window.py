@@ -155,3 +155,74 @@ def test_window_copy_lands_in_the_right_slot():
         assert (slots[(l % 3) * nfl:(l % 3 + 1) * nfl] == float(l + 1)).all()
         win.release(l)
     win.destroy()
+
+
+def test_windowed_prefill_equals_resident_prefill_bitwise():
+    """The window is byte-granular: bf16 prefill blobs (fp32 gains + bf16 matrices) pass through it the
+    same way, and a prompt run through windowed layers equals the resident run bit for bit."""
+    h, nq, nkv, d, sl = 256, 4, 2, 64, 344
+    n, L, W, max_seq = 40, 5, 2, 48
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq, dtype=B.TPI_BF16)
+    layout, nbytes = synth.blob_layout_bytes(h, nq, nkv, d, sl, 2)
+    rng = np.random.default_rng(77)
+    host = []
+    for l in range(L):
+        w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+        blob = torch.zeros(nbytes, dtype=torch.uint8).pin_memory()
+        for name, (off, shape, item) in layout.items():
+            t = torch.from_numpy(w[name].reshape(-1))
+            if item == 2:
+                t = t.to(torch.bfloat16)
+            blob[off:off + t.numel() * item] = t.view(torch.uint8)
+        host.append(blob)
+    x = torch.from_numpy(rng.standard_normal((n, h)).astype(np.float32)).cuda()
+
+    def views(base):
+        w = B.tpi_layer_weights()
+        for name, (off, _, _) in layout.items():
+            setattr(w, name, base + off)
+        return w
+
+    def run(get_layer, release_layer):
+        ws = torch.empty(B.tpi_workspace_bytes(cfg, n) // 4, device="cuda")
+        part = torch.empty((n, h), device="cuda")
+        s32, s16 = x.clone(), x.to(torch.bfloat16)
+        a32, a16 = torch.empty_like(s32), torch.empty_like(s16)
+        caches = []
+        for l in range(L):
+            K = torch.zeros((nkv, max_seq, d), device="cuda", dtype=torch.bfloat16); V = torch.zeros_like(K)
+            caches.append((K, V))
+            w = get_layer(l)
+            B.tpi_shard_layer_prefill(cfg, w, B.make_kv(K, V), 0, n, B.TPI_PHASE_ATTN, s16, part, ws)
+            B.tpi_star_reduce_bf16([part], s32, a32, a16)
+            B.tpi_shard_layer_prefill(cfg, w, None, 0, n, B.TPI_PHASE_FFN, a16, part, ws)
+            b32, b16 = torch.empty_like(s32), torch.empty_like(s16)
+            B.tpi_star_reduce_bf16([part], a32, b32, b16)
+            release_layer(l)
+            s32, s16 = b32, b16
+        torch.cuda.synchronize()
+        return s32, caches
+
+    dev_blobs = [b.cuda() for b in host]
+    ref, ref_kv = run(lambda l: views(dev_blobs[l].data_ptr()), lambda l: None)
+    slots = torch.empty(W * nbytes, dtype=torch.uint8, device="cuda")
+    win = B.Window(host, slots, W, nbytes)
+    for l in range(W):
+        win.prefetch(l)
+    issued = [W]
+
+    def release_layer(l):
+        win.release(l)
+        if issued[0] < L:
+            win.prefetch(issued[0])
+            issued[0] += 1
+
+    got, got_kv = run(lambda l: views(win.acquire(l)), release_layer)
+    ms, copied = win.copy_stats()
+    assert copied == L * nbytes
+    win.destroy()
+    assert torch.isfinite(ref).all()
+    assert torch.equal(got, ref)
+    for (Ka, Va), (Kb, Vb) in zip(got_kv, ref_kv):
+        assert torch.equal(Ka, Kb) and torch.equal(Va, Vb)
+
