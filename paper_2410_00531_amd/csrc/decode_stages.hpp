@@ -61,6 +61,42 @@ __device__ __forceinline__ void emit_row(const ShardView &s, const FusedReduce &
     rf.out[row] = acc;
 }
 
+// The same in two halves, for the row-parallel stages: the peers' values and the shortcut of the row a
+// thread will finish are requested when the kernel starts -- ahead of the weight stream in the in-order
+// memory pipe, so they cost no round trip at the end -- and summed once the shard's own value exists.
+struct PeerRow {
+    float v[kMaxBatchShards];
+    float res;
+};
+
+// Every load is unconditional -- slots without a peer read `dummy[row]` (any readable array of at least
+// row + 1 floats) and are ignored later: a load under a branch makes the compiler wait for all earlier
+// loads at the join, which would turn these requests into a chain of round trips.
+__device__ __forceinline__ void fetch_peers(const FusedReduce &rf, int row, const float *dummy, PeerRow &p)
+{
+#pragma unroll
+    for (int i = 0; i < kMaxBatchShards; ++i) {
+        const float *src = (i < rf.n && i != rf.rank) ? rf.peer[i] : dummy;
+        p.v[i] = src[row];
+    }
+    const float *rs = rf.residual ? rf.residual : dummy;
+    p.res = rs[row];
+}
+
+__device__ __forceinline__ void emit_row(const FusedReduce &rf, int row, float y, const PeerRow &p)
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxBatchShards; ++i) {
+        if (i < rf.n) {
+            float t = (i == rf.rank) ? y : p.v[i];
+            acc = (i == 0) ? t : acc + t;
+        }
+    }
+    if (rf.residual) acc = acc + p.res;
+    rf.out[row] = acc;
+}
+
 // cos | sin of pos * theta_e for e < d/2 into LDS (rope[e], rope[kRopeHalf + e]); thread e
 // computes entry e.  The angle reaches pos radians, so it is formed in fp64: fp32 would lose
 // the low bits of the phase.  Callers put a workgroup barrier between this and the first use.
@@ -147,13 +183,26 @@ __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView
     st.prefetch(vwg, nvwg, n_units, dq, rowfn);
     float4 xr[KCH];
     load_x_slice<KCH>(s.ws + a.ws_o, dq, xr);
-    // With the reduce folded in, a unit's sums wait in LDS and all rows of this workgroup are
-    // reduced together after the last unit.  The per-unit epilogue must not load anything: loads
-    // return in order, so waiting for a peer's value would also wait for the next units' weight
-    // batches that are already in flight, and the row pipeline would drain at every unit.
-    // (The launcher sizes the grid so that a workgroup owns at most 256 rows.)
-    __shared__ float ysave[kBlock];
+    // With the reduce folded in, thread i finishes row i of this workgroup's rows (the launcher sizes the
+    // grid so that a workgroup owns at most 256 rows).  Its peers' values are requested here, behind the
+    // first weight batch in the in-order memory pipe (ahead of it they would hold the weights back) and
+    // long before they are needed.
     constexpr bool fold = FOLD;      // compile-time: the plain stage carries none of the folding code
+    int my_row = -1;
+    PeerRow peers;
+    if constexpr (fold) {
+        if (vwg < n_units) {
+            const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
+            const int i = threadIdx.x;
+            const int row = (vwg + (i / ROWS) * nvwg) * ROWS + (i % ROWS);
+            if (i < my_rows && row < a.h) {
+                my_row = row;
+                fetch_peers(rf, row, s.w_o, peers);
+            }
+        }
+    }
+    // A unit's sums wait in LDS and all rows of the workgroup are reduced together after the last unit.
+    __shared__ float ysave[kBlock];
     auto epi = [&](int u, float (&y)[ROWS]) {
         if constexpr (fold) {
             const int r = threadIdx.x;
@@ -168,12 +217,7 @@ __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView
     st.run(xr, red, rowfn, epi);
     if constexpr (fold) if (vwg < n_units) {
         __syncthreads();
-        const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
-        const int i = threadIdx.x;
-        if (i < my_rows) {
-            const int row = (vwg + (i / ROWS) * nvwg) * ROWS + (i % ROWS);
-            if (row < a.h) emit_row(s, rf, row, ysave[i]);
-        }
+        if (my_row >= 0) emit_row(rf, my_row, ysave[threadIdx.x], peers);
     }
 }
 
@@ -227,13 +271,22 @@ __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView 
     st.prefetch(vwg, nvwg, n_units, a.sl, rowfn);
     float4 xr[KCH];
     load_x_slice<KCH>(s.ws + a.ws_act, a.sl, xr);
-    // With the reduce folded in, a unit's sums wait in LDS and all rows of this workgroup are
-    // reduced together after the last unit.  The per-unit epilogue must not load anything: loads
-    // return in order, so waiting for a peer's value would also wait for the next units' weight
-    // batches that are already in flight, and the row pipeline would drain at every unit.
-    // (The launcher sizes the grid so that a workgroup owns at most 256 rows.)
+    // see stage_oproj
+    constexpr bool fold = FOLD;
+    int my_row = -1;
+    PeerRow peers;
+    if constexpr (fold) {
+        if (vwg < n_units) {
+            const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
+            const int i = threadIdx.x;
+            const int row = (vwg + (i / ROWS) * nvwg) * ROWS + (i % ROWS);
+            if (i < my_rows && row < a.h) {
+                my_row = row;
+                fetch_peers(rf, row, s.w_down, peers);
+            }
+        }
+    }
     __shared__ float ysave[kBlock];
-    constexpr bool fold = FOLD;      // compile-time: the plain stage carries none of the folding code
     auto epi = [&](int u, float (&y)[ROWS]) {
         if constexpr (fold) {
             const int r = threadIdx.x;
@@ -248,12 +301,7 @@ __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView 
     st.run(xr, red, rowfn, epi);
     if constexpr (fold) if (vwg < n_units) {
         __syncthreads();
-        const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
-        const int i = threadIdx.x;
-        if (i < my_rows) {
-            const int row = (vwg + (i / ROWS) * nvwg) * ROWS + (i % ROWS);
-            if (row < a.h) emit_row(s, rf, row, ysave[i]);
-        }
+        if (my_row >= 0) emit_row(rf, my_row, ysave[threadIdx.x], peers);
     }
 }
 
