@@ -51,6 +51,10 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true", help="skip the bf16 prefill leg")
     ap.add_argument("--prefill-tokens", type=int, default=512)
     ap.add_argument("--prefill-steps", type=int, default=3)
+    ap.add_argument("--no-window-blocks", action="store_true",
+                    help="skip the block-granular window variants (attention / FFN blocks, FFN retention)")
+    ap.add_argument("--window-retain-every", type=int, default=2,
+                    help="T of the retention variant: the FFN block of every T-th layer stays resident")
     ap.add_argument("--no-window-prefill", action="store_true",
                     help="skip the windowed long-prompt prefill (the point where the copies can hide)")
     ap.add_argument("--window-prefill-tokens", type=int, default=16384)
@@ -170,15 +174,106 @@ def window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_
     finite = bool(torch.isfinite(out).all().item())
     win.destroy()
     copy_ms = L * nbytes / (link_gbps * 1e9) * 1e3
-    return {
+    res = {
         "workload": f"{m.name}-windowed-decode-one-shard", "window_layers": Wn, "steps": args.window_steps,
         "ms_per_token": round(ms, 2), "tokens_per_s": round(1e3 / ms, 3),
         "h2d_gb_per_token": round(L * nbytes / 1e9, 3), "pcie_gbps": round(L * nbytes / (ms * 1e-3) / 1e9, 2),
         "link_peak_gbps_plain_copy": round(link_gbps, 2),
         "pcie_frac_of_plain_copy": round(L * nbytes / (ms * 1e-3) / 1e9 / link_gbps, 4),
         "copy_ms_per_token_at_link_peak": round(copy_ms, 2), "resident_ms_per_token": round(ms_resident, 3),
-        "hidden_fraction": round(1.0 - (ms - ms_resident) / copy_ms, 4),
+        "hidden_fraction": round(max(0.0, 1.0 - (ms - ms_resident) / copy_ms), 4),
         "compute_over_copy": round(ms_resident / copy_ms, 4), "output_finite": finite,
+    }
+    if not args.no_window_blocks and Wn >= 2:
+        res["block_granular"] = [
+            window_blocks_variant(args, m, L, N, blobs, host, layout, cfg, KV_one, P_all, P_one, WS_one, h0, h_a, h_b,
+                                  h_attn, pos0, link_gbps, T)
+            for T in (0, args.window_retain_every)]
+    return res
+
+
+def window_blocks_variant(args, m, L, N, blobs, host, layout, cfg, KV_one, P_all, P_one, WS_one, h0, h_a, h_b, h_attn,
+                          pos0, link_gbps, T):
+    """The window at the paper's granularity: a window of w = --window-layers blocks, half of them attention
+    blocks and half FFN blocks (w/2 slots each), and -- for T > 0 -- block retention (Prop. 6): the FFN
+    block of every T-th layer is copied once and stays.  Decode is copy-bound here, so ms/token should
+    follow the bytes that still have to cross the link.  The retained blocks' device home is shard 0's own
+    region of the resident stack (identical bytes, no extra memory; the windowed run reads nothing else of it)."""
+    import torch
+
+    from paper_2410_00531_amd import binding as B
+    from paper_2410_00531_amd import synth
+    dev = h0.device
+    w = args.window_layers - args.window_layers % 2
+    n_a = layout["ffn_norm"][0]                                   # floats of the attention block
+    n_f = layout["w_down"][0] + layout["w_down"][2] - n_a         # floats of the FFN block
+    slots_a = torch.empty((w // 2) * n_a, dtype=torch.float32, device=dev)
+    slots_f = torch.empty((w // 2) * n_f, dtype=torch.float32, device=dev)
+    retained = {2 * l + 1 for l in range(L) if T > 0 and l % T == 0}
+    blocks = []
+    for l in range(L):
+        blocks.append((host[l][:n_a], n_a * 4, 0, None))
+        blocks.append((host[l][n_a:], n_f * 4, 1, blobs[l][0][n_a:] if (2 * l + 1) in retained else None))
+    win = B.Window.from_blocks(blocks, [(slots_a, n_a * 4, w // 2), (slots_f, n_f * 4, w // 2)])
+    lib = B.lib()
+    stream = torch.cuda.current_stream().cuda_stream
+    cfg_p = C.byref(cfg)
+    issued = [0]
+
+    def prefetch_next():
+        win.prefetch(issued[0] % (2 * L))
+        issued[0] += 1
+
+    for _ in range(w):
+        prefetch_next()
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError(B.tpi_last_error())
+
+    wv = (B.tpi_layer_weights * 1)()
+
+    def token(pos):
+        src, dst = h0, h_a
+        for l in range(L):
+            base = win.acquire(2 * l)
+            for name in ("attn_norm", "w_qkv", "w_o"):
+                setattr(wv[0], name, base + layout[name][0] * 4)
+            check(lib.tpi_shards_layer_decode(cfg_p, 1, wv, KV_one[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
+                                              P_one, WS_one, stream))
+            check(lib.tpi_star_reduce(P_all, N, m.hidden, src.data_ptr(), h_attn.data_ptr(), stream))
+            win.release(2 * l)
+            prefetch_next()
+            base = win.acquire(2 * l + 1)
+            for name in ("ffn_norm", "w_gate", "w_up", "w_down"):
+                setattr(wv[0], name, base + (layout[name][0] - n_a) * 4)
+            check(lib.tpi_shards_layer_decode(cfg_p, 1, wv, None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
+                                              P_one, WS_one, stream))
+            check(lib.tpi_star_reduce(P_all, N, m.hidden, h_attn.data_ptr(), dst.data_ptr(), stream))
+            win.release(2 * l + 1)
+            prefetch_next()
+            src, dst = dst, (h_b if dst is h_a else h_a)
+        return src
+
+    token(pos0)                                  # warm-up token: brings the retained blocks in
+    torch.cuda.synchronize()
+    _, bytes0 = win.copy_stats()
+    t = time.perf_counter()
+    for i in range(args.window_steps):
+        out = token(pos0 + 1 + i)
+    torch.cuda.current_stream().synchronize()
+    ms = (time.perf_counter() - t) * 1e3 / args.window_steps
+    _, bytes1 = win.copy_stats()
+    finite = bool(torch.isfinite(out).all().item())
+    win.destroy()
+    per_token = (bytes1 - bytes0) / args.window_steps
+    return {
+        "window_blocks": w, "retain_every": T, "retained_ffn_blocks": len(retained),
+        "retained_gb": round(len(retained) * n_f * 4 / 1e9, 2),
+        "window_slots_gb": round((w // 2) * (n_a + n_f) * 4 / 1e9, 3),
+        "ms_per_token": round(ms, 2), "h2d_gb_per_token": round(per_token / 1e9, 3),
+        "pcie_gbps": round(per_token / (ms * 1e-3) / 1e9, 2),
+        "copy_ms_per_token_at_link_peak": round(per_token / (link_gbps * 1e9) * 1e3, 2), "output_finite": finite,
     }
 
 

@@ -215,6 +215,45 @@ int tpi_window_acquire(tpi_window *w, int32_t layer, void *compute_stream,
 int tpi_window_release(tpi_window *w, int32_t layer, void *compute_stream);
 /* Blocks until every queued copy has finished, then frees the object. */
 int tpi_window_destroy(tpi_window *w);
+
+/*
+ * The same window at the paper's granularity (Sec. 3.3: "the memory scheduler
+ * asynchronously loads weights for either an attention or FFN block"; window
+ * size counted in blocks, Prop. 5) and with block retention (Prop. 6: "retain
+ * one FFN block in memory every T FFN blocks").
+ *
+ * A block is any contiguous run of bytes in pinned host memory; in the usual
+ * arrangement blocks 2l and 2l+1 are the attention block (attn_norm | w_qkv |
+ * w_o) and the FFN block (ffn_norm | w_gate | w_up | w_down) of layer l.
+ * Blocks of one slot class pass through that class's ring of equally sized
+ * HBM slots (class 0: attention blocks, class 1: FFN blocks; a window of w
+ * blocks, w even, is w/2 slots in each).  A retained block has a device home of
+ * its own (`resident`, caller-owned, `bytes` long): its first prefetch copies
+ * it there, later prefetches do nothing, acquire waits for that one copy and
+ * returns `resident`, release only checks the pairing.
+ *
+ * prefetch / acquire / release / copy_stats / destroy above take block indices
+ * for a window created here; ring order, states and errors are per slot class.
+ * The arrays are copied; host and device memory stay with the caller.
+ * TPI_EINVAL: counts < 1, null pointers, a block larger than its class's slot,
+ * slot class out of range, a retained block without `resident`.
+ */
+typedef struct tpi_window_block {
+    const void *host;     /* pinned host memory */
+    size_t bytes;
+    int32_t slot_class;   /* ignored for a retained block */
+    int32_t retained;     /* nonzero: copied once into `resident`, never evicted */
+    void *resident;       /* device memory for a retained block, NULL otherwise */
+} tpi_window_block;
+
+typedef struct tpi_window_slots {
+    void *base;           /* device memory, n_slots * slot_bytes */
+    size_t slot_bytes;
+    int32_t n_slots;
+} tpi_window_slots;
+
+int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_window_block *blocks,
+                             int32_t n_classes, const tpi_window_slots *classes);
 /* Total time (ms) the copy stream spent in copies between the first prefetch
  * and the last one completed so far, and the bytes they moved; synchronises
  * the copy stream.  Either output may be NULL. */

@@ -25,7 +25,8 @@ TPI_MAX_BATCH_SHARDS = 16
 EXPORTED = (
     "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode",
     "tpi_shard_layer_decode_reduce",
-    "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create", "tpi_window_prefetch",
+    "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create",
+    "tpi_window_create_blocks", "tpi_window_prefetch",
     "tpi_window_acquire", "tpi_window_release", "tpi_window_destroy", "tpi_window_copy_stats",
     "tpi_last_error", "tpi_abi_version", "tpi_prof_enable", "tpi_prof_read",
     "tpi_decoder_workspace_bytes", "tpi_decoder_create", "tpi_decoder_token", "tpi_decoder_status",
@@ -55,6 +56,15 @@ class tpi_layer_weights(C.Structure):
 
 class tpi_kv_layer(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p)]
+
+
+class tpi_window_block(C.Structure):
+    _fields_ = [("host", C.c_void_p), ("bytes", C.c_size_t), ("slot_class", C.c_int32),
+                ("retained", C.c_int32), ("resident", C.c_void_p)]
+
+
+class tpi_window_slots(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("slot_bytes", C.c_size_t), ("n_slots", C.c_int32)]
 
 
 _lib = None
@@ -99,6 +109,9 @@ def lib() -> C.CDLL:
         l.tpi_window_create.restype = C.c_int
         l.tpi_window_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_size_t,
                                         C.POINTER(C.c_void_p), C.c_void_p]
+        l.tpi_window_create_blocks.restype = C.c_int
+        l.tpi_window_create_blocks.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.POINTER(tpi_window_block),
+                                               C.c_int32, C.POINTER(tpi_window_slots)]
         for name in ("tpi_window_prefetch",):
             getattr(l, name).restype = C.c_int
             getattr(l, name).argtypes = [C.c_void_p, C.c_int32]
@@ -319,6 +332,23 @@ class Window:
         arr = (C.c_void_p * n)(*[_ptr(b) for b in host_blobs])
         _check(lib().tpi_window_create(C.byref(self._h), n, window_layers, layer_bytes, arr,
                                        _ptr(device_slots)))
+
+    @classmethod
+    def from_blocks(cls, blocks, classes) -> "Window":
+        """tpi_window_create_blocks.  blocks: sequence of (host_tensor, nbytes, slot_class, resident) with
+        ``resident`` a device tensor / address for a retained block, else None; classes: sequence of
+        (device_tensor, slot_bytes, n_slots).  Block indices then take the place of layer indices."""
+        self = cls.__new__(cls)
+        self._h = C.c_void_p()
+        self._keep = (list(blocks), list(classes))
+        barr = (tpi_window_block * len(blocks))()
+        for i, (host, nbytes, slot_class, resident) in enumerate(blocks):
+            barr[i] = tpi_window_block(_ptr(host), nbytes, slot_class, 1 if resident is not None else 0, _ptr(resident))
+        carr = (tpi_window_slots * len(classes))()
+        for i, (base, slot_bytes, n_slots) in enumerate(classes):
+            carr[i] = tpi_window_slots(_ptr(base), slot_bytes, n_slots)
+        _check(lib().tpi_window_create_blocks(C.byref(self._h), len(blocks), barr, len(classes), carr))
+        return self
 
     def prefetch(self, layer: int) -> None:
         _check(lib().tpi_window_prefetch(self._h, layer))

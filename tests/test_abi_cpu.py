@@ -32,6 +32,8 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(B.tpi_shard_cfg) == 36
     assert C.sizeof(B.tpi_layer_weights) == 56
     assert C.sizeof(B.tpi_kv_layer) == 16
+    assert C.sizeof(B.tpi_window_block) == 32
+    assert C.sizeof(B.tpi_window_slots) == 24
 
 
 def _w():
@@ -110,6 +112,23 @@ def test_window_argument_errors_without_a_device():
     assert lib.tpi_window_create(C.byref(h), 2, 1, 16, None, FAKE) == B.TPI_EINVAL
     arr2 = (C.c_void_p * 2)(FAKE, None)
     assert lib.tpi_window_create(C.byref(h), 2, 1, 16, arr2, FAKE) == B.TPI_EINVAL
+    # block-granular creation: every malformed description is refused before any HIP call
+    blk = lambda host=FAKE, nbytes=16, cls=0, retained=0, resident=None: B.tpi_window_block(host, nbytes, cls, retained, resident)
+    one_class = (B.tpi_window_slots * 1)(B.tpi_window_slots(FAKE, 16, 2))
+    mk = lambda *bs: (B.tpi_window_block * len(bs))(*bs)
+    cb = lib.tpi_window_create_blocks
+    assert cb(C.byref(h), 0, mk(blk()), 1, one_class) == B.TPI_EINVAL
+    assert cb(C.byref(h), 1, mk(blk()), 0, one_class) == B.TPI_EINVAL
+    assert cb(C.byref(h), 1, None, 1, one_class) == B.TPI_EINVAL
+    assert cb(C.byref(h), 1, mk(blk()), 1, None) == B.TPI_EINVAL
+    assert cb(C.byref(h), 1, mk(blk(host=None)), 1, one_class) == B.TPI_EINVAL
+    assert cb(C.byref(h), 1, mk(blk(nbytes=0)), 1, one_class) == B.TPI_EINVAL
+    assert cb(C.byref(h), 1, mk(blk(nbytes=17)), 1, one_class) == B.TPI_EINVAL          # larger than its slot
+    assert b"do not fit" in lib.tpi_last_error()
+    assert cb(C.byref(h), 1, mk(blk(cls=1)), 1, one_class) == B.TPI_EINVAL              # class out of range
+    assert cb(C.byref(h), 1, mk(blk(retained=1)), 1, one_class) == B.TPI_EINVAL         # retained, no home
+    assert cb(C.byref(h), 1, mk(blk()), 1, (B.tpi_window_slots * 1)(B.tpi_window_slots(FAKE, 16, 0))) == B.TPI_EINVAL
+    assert cb(C.byref(h), 1, mk(blk()), 1, (B.tpi_window_slots * 1)(B.tpi_window_slots(None, 16, 1))) == B.TPI_EINVAL
     assert lib.tpi_window_prefetch(None, 0) == B.TPI_EINVAL
     assert lib.tpi_window_destroy(None) == B.TPI_EINVAL
 

@@ -226,3 +226,119 @@ def test_windowed_prefill_equals_resident_prefill_bitwise():
     for (Ka, Va), (Kb, Vb) in zip(got_kv, ref_kv):
         assert torch.equal(Ka, Kb) and torch.equal(Va, Vb)
 
+
+ATTN_TENSORS = ("attn_norm", "w_qkv", "w_o")
+FFN_TENSORS = ("ffn_norm", "w_gate", "w_up", "w_down")
+
+
+def _block_layout(shapes, names):
+    off, out = 0, {}
+    for name in names:
+        n = int(np.prod(shapes[name]))
+        out[name] = (off, n)
+        off += n
+    return out, off
+
+
+@pytest.mark.parametrize("L,w,T", [(5, 4, 0), (6, 2, 0), (6, 4, 2), (7, 4, 3), (4, 2, 1)])
+def test_block_window_with_retention_equals_resident_run_bitwise(L, w, T):
+    """The window at the paper's granularity: blocks 2l / 2l+1 are layer l's attention / FFN block, a window
+    of w blocks is w/2 attention slots and w/2 FFN slots, and every T-th FFN block (layers 0, T, 2T, ...)
+    is retained: copied once, never again.  Outputs equal the resident run bit for bit and the bytes copied
+    are exactly the non-retained blocks per token plus the retained ones once."""
+    h, nq, nkv, d, sl = 512, 4, 2, 64, 1024
+    pos0, n_tokens, max_seq = 9, 3, 16
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq)
+    shapes = synth.shard_tensor_shapes(h, nq, nkv, d, sl)
+    lay_a, n_a = _block_layout(shapes, ATTN_TENSORS)
+    lay_f, n_f = _block_layout(shapes, FFN_TENSORS)
+    rng = np.random.default_rng(100 * L + 10 * w + T)
+    host = []                                   # block index 2l: attention, 2l+1: FFN
+    for l in range(L):
+        wts = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+        for lay, n in ((lay_a, n_a), (lay_f, n_f)):
+            blob = torch.empty(n, dtype=torch.float32).pin_memory()
+            for name, (off, cnt) in lay.items():
+                blob[off:off + cnt] = torch.from_numpy(wts[name].reshape(-1))
+            host.append(blob)
+    h0 = torch.from_numpy(rng.standard_normal(h).astype(np.float32)).cuda()
+
+    def fresh_kv():
+        g = torch.Generator(device="cuda"); g.manual_seed(5)
+        keep = []
+        for l in range(L):
+            K = torch.zeros((nkv, max_seq, d), device="cuda"); V = torch.zeros_like(K)
+            K[:, :pos0] = torch.randn((nkv, pos0, d), generator=g, device="cuda")
+            V[:, :pos0] = torch.randn((nkv, pos0, d), generator=g, device="cuda")
+            keep.append((K, V))
+        return keep, [B.make_kv(K, V) for K, V in keep]
+
+    def weights(attn_base, ffn_base):
+        wv = B.tpi_layer_weights()
+        for name, (off, _) in lay_a.items():
+            setattr(wv, name, attn_base + off * 4)
+        for name, (off, _) in lay_f.items():
+            setattr(wv, name, ffn_base + off * 4)
+        return wv
+
+    def run(get_block, release_block):
+        x = h0.clone()
+        part = torch.empty_like(x); h_attn = torch.empty_like(x); out = torch.empty_like(x)
+        ws = torch.empty(B.tpi_workspace_bytes(cfg, 1) // 4, device="cuda")
+        keep, kv = fresh_kv()
+        outs, src = [], x
+        for t in range(n_tokens):
+            for l in range(L):
+                wa = weights(get_block(2 * l), 0)
+                B.tpi_shard_layer_decode(cfg, wa, kv[l], pos0 + t, B.TPI_PHASE_ATTN, src, part, ws)
+                B.tpi_star_reduce([part], src, h_attn)
+                release_block(2 * l)
+                wf = weights(0, get_block(2 * l + 1))
+                B.tpi_shard_layer_decode(cfg, wf, None, pos0 + t, B.TPI_PHASE_FFN, h_attn, part, ws)
+                B.tpi_star_reduce([part], h_attn, out)
+                release_block(2 * l + 1)
+                src = out.clone()
+            outs.append(src.clone())
+        torch.cuda.synchronize()
+        return outs
+
+    dev = [b.cuda() for b in host]
+    ref = run(lambda b: dev[b].data_ptr(), lambda b: None)
+
+    retained = {2 * l + 1 for l in range(L) if T > 0 and l % T == 0}
+    homes = {b: torch.empty(n_f, device="cuda") for b in retained}
+    slots_a = torch.empty((w // 2) * n_a, device="cuda")
+    slots_f = torch.empty((w // 2) * n_f, device="cuda")
+    blocks = [(host[b], host[b].numel() * 4, b % 2, homes.get(b)) for b in range(2 * L)]
+    win = B.Window.from_blocks(blocks, [(slots_a, n_a * 4, w // 2), (slots_f, n_f * 4, w // 2)])
+    total = 2 * L * n_tokens
+    issued = [0]
+
+    def prefetch_next():
+        if issued[0] < total:
+            win.prefetch(issued[0] % (2 * L))
+            issued[0] += 1
+
+    for _ in range(w):
+        prefetch_next()
+
+    def release_block(b):
+        win.release(b)
+        prefetch_next()
+
+    got = run(lambda b: win.acquire(b), release_block)
+    _, copied = win.copy_stats()
+    per_token = L * n_a * 4 + sum(n_f * 4 for l in range(L) if (2 * l + 1) not in retained)
+    assert copied == n_tokens * per_token + len(retained) * n_f * 4
+    # protocol on a retained block: release without acquire is refused, a repeated prefetch is free
+    if retained:
+        b = min(retained)
+        with pytest.raises(B.TpiError) as ei:
+            win.release(b)
+        assert ei.value.code == B.TPI_ESTATE
+        win.prefetch(b)
+        assert win.copy_stats()[1] == copied
+    win.destroy()
+    for a, r in zip(got, ref):
+        assert torch.equal(a, r)
+
