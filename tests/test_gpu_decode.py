@@ -275,3 +275,41 @@ def test_star_reduce_order_unaligned_and_aliasing():
     assert np.array_equal(res.cpu().numpy().view(np.uint32), O.reduce_seq_f32(ps, ps[0]).view(np.uint32))
     # zero length is a no-op
     B.tpi_star_reduce(tp, None, out, length=0)
+
+
+def test_layer_with_uneven_shares_matches_oracle():
+    """Sec. 3.1 lets device i hold a proportion p_i of the heads and FFN columns.  Three shards with
+    4 / 2 / 2 query heads, 2 / 1 / 1 KV heads and 1100 / 600 / 348 FFN columns, each with its own shard
+    configuration, run phase by phase through the library; partials, reduces and caches must match the
+    oracle run on the same shards."""
+    h, d, max_seq, pos = 512, 64, 40, 33
+    split = [(4, 2, 1100), (2, 1, 600), (2, 1, 348)]
+    rng = np.random.default_rng(808)
+    x = rng.standard_normal(h).astype(np.float32)
+    cfgs, ws, caches, gsh = [], [], [], []
+    for nq, nkv, sl in split:
+        cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq)
+        w, K, V = random_shard_np(rng, cfg, pos)
+        cfgs.append(cfg); ws.append(w); caches.append((K.copy(), V.copy()))
+        gsh.append(GpuShard(cfg, w, K, V))
+    xt = torch.from_numpy(x).cuda()
+    h_attn = torch.empty_like(xt); h_out = torch.empty_like(xt)
+    for cfg, s in zip(cfgs, gsh):
+        B.tpi_shard_layer_decode(cfg, s.weights, s.kv, pos, B.TPI_PHASE_ATTN, xt, s.partial, s.ws)
+    B.tpi_star_reduce([s.partial for s in gsh], xt, h_attn)
+    for cfg, s in zip(cfgs, gsh):
+        B.tpi_shard_layer_decode(cfg, s.weights, None, pos, B.TPI_PHASE_FFN, h_attn, s.partial, s.ws)
+    B.tpi_star_reduce([s.partial for s in gsh], h_attn, h_out)
+    torch.cuda.synchronize()
+    pa = [O.attn_block(ocfg(c), w["attn_norm"], w["w_qkv"], w["w_o"], kv[0], kv[1], pos, x).astype(np.float32)
+          for c, w, kv in zip(cfgs, ws, caches)]
+    ref_attn = O.reduce_seq_f32(pa, x)
+    pf = [O.ffn_block(ocfg(c), w["ffn_norm"], w["w_gate"], w["w_up"], w["w_down"], ref_attn).astype(np.float32)
+          for c, w in zip(cfgs, ws)]
+    ref_out = O.reduce_seq_f32(pf, ref_attn)
+    assert rel_err(h_attn.cpu().numpy(), ref_attn) <= FP32_TOL
+    assert rel_err(h_out.cpu().numpy(), ref_out) <= FP32_TOL
+    for s, (Ko, Vo) in zip(gsh, caches):
+        assert rel_err(s.K.cpu().numpy()[:, pos], Ko[:, pos]) <= FP32_TOL
+        assert rel_err(s.V.cpu().numpy()[:, pos], Vo[:, pos]) <= FP32_TOL
+

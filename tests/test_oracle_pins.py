@@ -120,6 +120,57 @@ def test_tp_identity_against_unsharded_torch_layer(N, a, b):
     np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12 * np.abs(ref).max() + 1e-14)
 
 
+def slice_uneven_shard(full, q0, q1, k0, k1, f0, f1, d):
+    """A shard that owns query heads [q0, q1), KV heads [k0, k1) and FFN columns [f0, f1): the split by
+    unequal proportions p_i of Sec. 3.1."""
+    qs, ks, fs = slice(q0 * d, q1 * d), slice(k0 * d, k1 * d), slice(f0, f1)
+    return {"attn_norm": full["attn_norm"],
+            "w_qkv": np.concatenate([full["w_q"][qs], full["w_k"][ks], full["w_v"][ks]], 0),
+            "w_o": np.ascontiguousarray(full["w_o"][:, qs]),
+            "ffn_norm": full["ffn_norm"],
+            "w_gate": full["w_gate"][fs], "w_up": full["w_up"][fs],
+            "w_down": np.ascontiguousarray(full["w_down"][:, fs])}
+
+
+# heads per shard (query, KV) and FFN columns per shard: proportions 1/2, 1/4, 1/4 and a ragged FFN split
+UNEVEN_SPLIT = dict(a=8, b=4, d=16, s=160, q=(4, 2, 2), kv=(2, 1, 1), f=(70, 50, 40))
+
+
+def test_tp_identity_with_uneven_shares():
+    """Devices may hold unequal proportions p_i of the heads and FFN columns (Sec. 3.1); the sum of the
+    shard partials is still the unsharded layer."""
+    u = UNEVEN_SPLIT
+    a, b, d, s = u["a"], u["b"], u["d"], u["s"]
+    rng = np.random.default_rng(4242)
+    h, T, max_seq = 96, 7, 10
+    full = make_full_layer(rng, h, a, b, d, s)
+    x = rng.standard_normal(h).astype(np.float32)
+    Kfull = np.zeros((b, max_seq, d), np.float32); Vfull = np.zeros_like(Kfull)
+    Kfull[:, :T] = rng.standard_normal((b, T, d)); Vfull[:, :T] = rng.standard_normal((b, T, d))
+    Kt, Vt = torch.tensor(Kfull.copy()), torch.tensor(Vfull.copy())
+    ref_attn, ref_ffn = dense_layer_torch(x, full, Kt, Vt, T, a, b, d)
+    pa, shards, cfgs = [], [], []
+    q0 = k0 = f0 = 0
+    for nq, nkv, sl in zip(u["q"], u["kv"], u["f"]):
+        sh = slice_uneven_shard(full, q0, q0 + nq, k0, k0 + nkv, f0, f0 + sl, d)
+        cfg = O.ShardCfg(h, nq, nkv, d, sl, max_seq)
+        K = np.ascontiguousarray(Kfull[k0:k0 + nkv]); V = np.ascontiguousarray(Vfull[k0:k0 + nkv])
+        pa.append(O.attn_block(cfg, sh["attn_norm"], sh["w_qkv"], sh["w_o"], K, V, T, x))
+        shards.append(sh); cfgs.append(cfg)
+        q0 += nq; k0 += nkv; f0 += sl
+    assert (q0, k0, f0) == (a, b, s)
+    h_attn = O.reduce_f64(pa, x)
+    np.testing.assert_allclose(h_attn, ref_attn, rtol=0, atol=1e-12 * np.abs(ref_attn).max() + 1e-14)
+    h_attn32 = ref_attn.astype(np.float32)
+    t = lambda v: torch.as_tensor(np.asarray(v), dtype=torch.float64)
+    xn2 = t(h_attn32) * torch.rsqrt(t(h_attn32).pow(2).mean() + 1e-5) * t(full["ffn_norm"])
+    ref = (F.linear(F.silu(F.linear(xn2, t(full["w_gate"]))) * F.linear(xn2, t(full["w_up"])),
+                    t(full["w_down"])) + t(h_attn32)).numpy()
+    pf = [O.ffn_block(c, sh["ffn_norm"], sh["w_gate"], sh["w_up"], sh["w_down"], h_attn32)
+          for c, sh in zip(cfgs, shards)]
+    np.testing.assert_allclose(O.reduce_f64(pf, h_attn32), ref, rtol=0, atol=1e-12 * np.abs(ref).max() + 1e-14)
+
+
 def test_brute_force_hand_sized_case():
     """h = 4, one head per shard, d = 2, 4 FFN columns per shard, N = 2:
     every step written as an einsum over explicit index expressions."""
