@@ -204,3 +204,51 @@ def layer_decode(cfg: ShardCfg, shards, kv, pos, h_in):
           .astype(np.float32) for s in shards]
     h_ffn = reduce_seq_f32(pf, h_attn)
     return h_ffn, h_attn, pa, pf
+
+
+# ---------------------------------------------------------------------------
+# The ends of the token loop, master only (Alg. 1 "Preprocess" and "Postprocess"; Sec. 3.1 Step 4:
+# the summed output passes the final norm and the task head, softmax gives the distribution of the
+# next token, which is then sampled).
+# ---------------------------------------------------------------------------
+
+def embed_token(w_emb, token):
+    """Input embedding of one token index: row `token` of W_emb [vocab][h]."""
+    w_emb = np.asarray(w_emb)
+    if not 0 <= token < w_emb.shape[0]:
+        raise ValueError("token outside the vocabulary")
+    return np.array(w_emb[token], dtype=np.float32, copy=True)
+
+
+def lm_head(final_norm, w_head, h_in, eps=1e-5):
+    """logits[v] = W_head[v] . rmsnorm(h_in) (fp64)."""
+    return matvec(w_head, rmsnorm(h_in, final_norm, eps))
+
+
+def softmax(logits):
+    z = np.asarray(logits, np.float64)
+    e = np.exp(z - z.max())
+    return e / e.sum()
+
+
+def greedy_token(logits):
+    """Index of the largest logit, the lowest index among equals."""
+    z = np.asarray(logits)
+    best = 0
+    for i in range(1, z.shape[0]):
+        if z[i] > z[best]:
+            best = i
+    return best
+
+
+def sample_token(logits, u):
+    """Inverse-CDF sampling with a uniform draw u in [0, 1) supplied by the caller: the first index whose
+    cumulative probability exceeds u (the last index if rounding leaves the total below u)."""
+    p = softmax(logits)
+    acc = 0.0
+    for i in range(p.shape[0]):
+        acc += p[i]
+        if acc > u:
+            return i
+    return p.shape[0] - 1
+

@@ -489,3 +489,39 @@ def test_tiny_config_layer_stack_matches_unsharded_stack():
         # fp32 interface roundings on the oracle side: a few ulp of the running magnitude
         np.testing.assert_allclose(x, ref, rtol=0, atol=2e-6 * np.abs(ref).max())
         xd = ref.astype(np.float32)
+
+
+def test_token_ends_embedding_head_and_token_choice():
+    """Ends of the token loop (Sec. 3.1 Step 4; Alg. 1 Preprocess / Postprocess) against library routines,
+    closed forms and brute force."""
+    rng = np.random.default_rng(31)
+    v, h = 53, 40
+    w_emb = rng.standard_normal((v, h)).astype(np.float32)
+    assert np.array_equal(O.embed_token(w_emb, 17), w_emb[17])
+    with pytest.raises(ValueError):
+        O.embed_token(w_emb, v)
+    g = (1 + 0.1 * rng.standard_normal(h)).astype(np.float32)
+    w_head = rng.standard_normal((v, h)).astype(np.float32)
+    x = rng.standard_normal(h).astype(np.float32)
+    t = lambda a: torch.as_tensor(np.asarray(a), dtype=torch.float64)
+    ref = F.linear(t(x) * torch.rsqrt(t(x).pow(2).mean() + 1e-5) * t(g), t(w_head)).numpy()
+    logits = O.lm_head(g, w_head, x)
+    np.testing.assert_allclose(logits, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+    # softmax: library routine, sum to one, shift invariance
+    p = O.softmax(logits)
+    np.testing.assert_allclose(p, torch.softmax(t(logits), 0).numpy(), rtol=1e-13, atol=0)
+    assert abs(p.sum() - 1.0) < 1e-14
+    np.testing.assert_allclose(O.softmax(logits + 1000.0), p, rtol=1e-10)
+    # greedy: numpy's argmax (first occurrence), ties resolved to the lowest index
+    assert O.greedy_token(logits) == int(np.argmax(logits))
+    assert O.greedy_token(np.array([1.0, 3.0, 3.0, 2.0])) == 1
+    # inverse CDF: brute force against the cumulative sums, edges, and the frequencies of many draws
+    cdf = np.cumsum(p)
+    for u in (0.0, 0.25, 0.5, 0.999999, float(cdf[10]), float(np.nextafter(cdf[10], 0.0))):
+        k = O.sample_token(logits, u)
+        assert (cdf[k] > u or k == v - 1) and (k == 0 or cdf[k - 1] <= u)
+    assert O.sample_token(np.array([0.0, 0.0]), 0.49) == 0 and O.sample_token(np.array([0.0, 0.0]), 0.51) == 1
+    us = (np.arange(20000) + 0.5) / 20000
+    counts = np.bincount([O.sample_token(logits, float(u)) for u in us], minlength=v)
+    np.testing.assert_allclose(counts / 20000, p, atol=1.5 / 20000 + 1e-12)
+
