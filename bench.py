@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true", help="skip the bf16 prefill leg")
     ap.add_argument("--prefill-tokens", type=int, default=512)
     ap.add_argument("--prefill-steps", type=int, default=3)
+    ap.add_argument("--no-token-ends", action="store_true", help="skip embedding / task head / token choice")
+    ap.add_argument("--vocab", type=int, default=32000)
     ap.add_argument("--no-window-blocks", action="store_true",
                     help="skip the block-granular window variants (attention / FFN blocks, FFN retention)")
     ap.add_argument("--window-retain-every", type=int, default=2,
@@ -99,6 +101,47 @@ def token_bytes(m, n_shards, n_reduce, n_layers, pos):
     sb = stage_bytes(m, n_shards, pos)
     reduce_b = (n_reduce + 2) * m.hidden * 4          # N partials + shortcut read, one write
     return n_layers * (sum(sb.values()) + 2 * reduce_b)
+
+
+def token_ends_leg(args, m, ms_token):
+    """The master's share outside the layers (Alg. 1 Preprocess / Postprocess): embedding row, final norm +
+    task head (a streaming GEMV over vocab x hidden fp32), softmax + token choice.  Vocabulary 32000 as in
+    the Llama 2 models of the paper's model table."""
+    import torch
+
+    from paper_2410_00531_amd import binding as B
+    dev = torch.device("cuda:0")
+    vocab, h = args.vocab, m.hidden
+    gen = torch.Generator(device=dev); gen.manual_seed(args.seed + 3)
+    w_head = torch.empty((vocab, h), dtype=torch.float32, device=dev).normal_(0.0, 0.02, generator=gen)
+    norm = torch.empty(h, dtype=torch.float32, device=dev).normal_(1.0, 0.02, generator=gen)
+    x = torch.randn(h, generator=gen, device=dev)
+    logits = torch.empty(vocab, dtype=torch.float32, device=dev)
+    tok = torch.zeros(1, dtype=torch.int32, device=dev)
+    hx = torch.empty(h, dtype=torch.float32, device=dev)
+
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    us_head = timed(lambda: B.tpi_lm_head(norm, w_head, x, logits, m.rms_eps))
+    us_pick = timed(lambda: B.tpi_next_token(logits, 0.5, tok))
+    us_emb = timed(lambda: B.tpi_embed_token(w_head, 17, hx))      # any [vocab][hidden] table serves as W_emb here
+    head_bytes = (vocab * h + 2 * h + vocab) * 4
+    ends_ms = (us_head + us_pick + us_emb) / 1e3
+    return {
+        "vocab": vocab, "lm_head_us": round(us_head, 1), "lm_head_gb": round(head_bytes / 1e9, 3),
+        "lm_head_gbps": round(head_bytes / (us_head * 1e-6) / 1e9, 1),
+        "lm_head_frac_of_peak": round(head_bytes / (us_head * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+        "next_token_us": round(us_pick, 1), "embed_us": round(us_emb, 1),
+        "ms_per_token_with_ends": round(ms_token + ends_ms, 4), "token": int(tok.item()),
+    }
 
 
 def window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_one, WS_one, h0, h_a, h_b, h_attn,
@@ -763,6 +806,10 @@ def main():
         persistent["hbm_frac_of_peak"] = round(persistent["hbm_gbps"] / HBM_PEAK_GBPS, 4)
         persistent["kernel_hbm_frac_of_peak"] = round(bytes_p / (persistent["kernel_avg_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
         result["one_shard_persistent"] = persistent
+
+    # ---- the master's work outside the layers --------------------------------------------------------
+    if not args.no_token_ends:
+        result["token_ends"] = token_ends_leg(args, m, result["value"])
 
     # ---- one shard with its weights streamed through a sliding window (pinned host -> HBM) --------
     if not args.no_window and args.mode in ("both", "one"):

@@ -260,6 +260,33 @@ int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_windo
 int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes);
 
 /*
+ * The ends of the token loop, run by the master device only (Alg. 1,
+ * "Preprocess" and "Postprocess"; Sec. 3.1 Step 4).  All pointers are device
+ * pointers; nothing is allocated, nothing synchronises.
+ *
+ * tpi_embed_token: h_out[hidden] = row `token` of w_emb [vocab][hidden] (fp32),
+ *   the input embedding of the token that was just chosen.
+ * tpi_lm_head: logits[v] = w_head[v] . rmsnorm(h_in; final_norm, rms_eps) for
+ *   v < vocab; w_head [vocab][hidden] fp32 row-major, read once (a streaming
+ *   GEMV like the decode stages).  hidden a multiple of 4, at most 16384;
+ *   final_norm, w_head, h_in 16-byte aligned (else TPI_EUNSUPPORTED).
+ * tpi_next_token: softmax over logits[vocab]; probs (nullable) receives the
+ *   distribution; *token_out (device int32) receives the next token:
+ *   u < 0  -> the index of the largest logit, the lowest index among equals;
+ *   0 <= u < 1 -> inverse-CDF sampling with the caller's uniform draw u: the
+ *   first index whose cumulative probability exceeds u (sums in fp32, index
+ *   order).  The library draws no random numbers.
+ * TPI_EINVAL: null pointers, vocab < 1, token outside [0, vocab), hidden not a
+ * positive multiple of 4, rms_eps <= 0, u >= 1.
+ */
+int tpi_embed_token(const float *w_emb, int32_t vocab, int32_t hidden, int32_t token,
+                    float *h_out, void *stream);
+int tpi_lm_head(const float *final_norm, const float *w_head, int32_t vocab, int32_t hidden,
+                float rms_eps, const float *h_in, float *logits, void *stream);
+int tpi_next_token(const float *logits, int32_t vocab, float u, float *probs,
+                   int32_t *token_out, void *stream);
+
+/*
  * Whole-token decode of ONE device's shard (Alg. 2, the worker's loop over all
  * decoder layers of one token) in a single persistent launch: per layer the
  * attention block, the star reduce with the shortcut, the FFN block and the

@@ -27,6 +27,7 @@ EXPORTED = (
     "tpi_shard_layer_decode_reduce",
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create",
     "tpi_window_create_blocks", "tpi_window_prefetch",
+    "tpi_embed_token", "tpi_lm_head", "tpi_next_token",
     "tpi_window_acquire", "tpi_window_release", "tpi_window_destroy", "tpi_window_copy_stats",
     "tpi_last_error", "tpi_abi_version", "tpi_prof_enable", "tpi_prof_read",
     "tpi_decoder_workspace_bytes", "tpi_decoder_create", "tpi_decoder_token", "tpi_decoder_status",
@@ -123,6 +124,13 @@ def lib() -> C.CDLL:
         l.tpi_window_destroy.argtypes = [C.c_void_p]
         l.tpi_window_copy_stats.restype = C.c_int
         l.tpi_window_copy_stats.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
+        l.tpi_embed_token.restype = C.c_int
+        l.tpi_embed_token.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        l.tpi_lm_head.restype = C.c_int
+        l.tpi_lm_head.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
+                                  C.c_void_p]
+        l.tpi_next_token.restype = C.c_int
+        l.tpi_next_token.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
         l.tpi_prof_enable.restype = C.c_int
         l.tpi_prof_enable.argtypes = [C.c_int, C.c_int32]
         l.tpi_prof_read.restype = C.c_int
@@ -318,6 +326,22 @@ class Decoder:
             self.destroy()
         except Exception:
             pass
+
+
+def tpi_embed_token(w_emb, token: int, h_out, stream=None) -> None:
+    """w_emb: [vocab][hidden] fp32 tensor."""
+    _check(lib().tpi_embed_token(_ptr(w_emb), w_emb.shape[0], w_emb.shape[1], token, _ptr(h_out), _stream(stream)))
+
+
+def tpi_lm_head(final_norm, w_head, h_in, logits, rms_eps: float = 1e-5, stream=None) -> None:
+    """w_head: [vocab][hidden] fp32 tensor; logits: [vocab] fp32."""
+    _check(lib().tpi_lm_head(_ptr(final_norm), _ptr(w_head), w_head.shape[0], w_head.shape[1], rms_eps, _ptr(h_in),
+                             _ptr(logits), _stream(stream)))
+
+
+def tpi_next_token(logits, u: float, token_out, probs=None, stream=None) -> None:
+    """u < 0: largest logit; 0 <= u < 1: inverse CDF at u.  token_out: int32 device tensor of one element."""
+    _check(lib().tpi_next_token(_ptr(logits), logits.numel(), u, _ptr(probs), _ptr(token_out), _stream(stream)))
 
 
 class Window:

@@ -141,3 +141,24 @@ def test_whole_token_kernel_is_reported_unavailable():
     rc = B.lib().tpi_decoder_create(C.byref(h), C.byref(cfg), 1, w, kv, 1, 0, None, None, 0x10000, 0)
     assert rc == B.TPI_EUNSUPPORTED and "switched off" in B.tpi_last_error()
     assert B.lib().tpi_decoder_create(C.byref(h), C.byref(cfg), 0, w, kv, 1, 0, None, None, 0x10000, 0) == B.TPI_EINVAL
+
+
+def test_token_ends_argument_errors_without_a_device():
+    lib = B.lib()
+    assert lib.tpi_embed_token(None, 10, 8, 0, FAKE, None) == B.TPI_EINVAL
+    assert lib.tpi_embed_token(FAKE, 10, 8, 10, FAKE, None) == B.TPI_EINVAL       # token outside the vocabulary
+    assert lib.tpi_embed_token(FAKE, 10, 8, -1, FAKE, None) == B.TPI_EINVAL
+    assert lib.tpi_embed_token(FAKE, 0, 8, 0, FAKE, None) == B.TPI_EINVAL
+    head = lambda norm=FAKE, w=FAKE, v=10, h=8, eps=1e-5, x=FAKE, out=FAKE: lib.tpi_lm_head(norm, w, v, h, eps, x, out, None)
+    assert head(norm=None) == B.TPI_EINVAL and head(out=None) == B.TPI_EINVAL
+    assert head(v=0) == B.TPI_EINVAL
+    assert head(h=6) == B.TPI_EINVAL and head(h=0) == B.TPI_EINVAL
+    assert head(eps=0.0) == B.TPI_EINVAL
+    assert head(h=16388) == B.TPI_EUNSUPPORTED
+    assert head(w=FAKE + 4) == B.TPI_EUNSUPPORTED
+    assert lib.tpi_next_token(None, 10, 0.5, None, FAKE, None) == B.TPI_EINVAL
+    assert lib.tpi_next_token(FAKE, 10, 0.5, None, None, None) == B.TPI_EINVAL
+    assert lib.tpi_next_token(FAKE, 0, 0.5, None, FAKE, None) == B.TPI_EINVAL
+    assert lib.tpi_next_token(FAKE, 10, 1.0, None, FAKE, None) == B.TPI_EINVAL
+    assert lib.tpi_next_token(FAKE, 10, float("nan"), None, FAKE, None) == B.TPI_EINVAL
+
