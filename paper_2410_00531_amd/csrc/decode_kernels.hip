@@ -119,10 +119,21 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
     {
         const int npairs = (a.nq + 2 * a.nkv) * (a.d / 2);
         ProfScope ps(kStageQkv, st);
+        // One rotary pair per unit keeps a single shard's grid large enough to balance over the chip; with
+        // several shards per launch there are workgroups to spare, and two pairs per unit halve the
+        // per-workgroup prologue (input slice, norm, rotary table).
+        const bool fat = (long)npairs * n_shards >= 4096;
         TPI_KCH_SWITCH(a.h, {
-            constexpr int PAIRS = WIDE ? 4 : 1;
-            int gx = balanced_grid(cdiv(npairs, PAIRS));
-            hipLaunchKernelGGL((k_qkv_rope<PAIRS, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            if (WIDE) {
+                int gx = balanced_grid(cdiv(npairs, 4));
+                hipLaunchKernelGGL((k_qkv_rope<4, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            } else if (fat) {
+                int gx = balanced_grid(cdiv(npairs, 2));
+                hipLaunchKernelGGL((k_qkv_rope<2, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            } else {
+                int gx = balanced_grid(cdiv(npairs, 1));
+                hipLaunchKernelGGL((k_qkv_rope<1, KCH, UB>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            }
         })
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
