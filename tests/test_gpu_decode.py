@@ -228,6 +228,74 @@ def test_70b_shaped_layer_all_shards():
         assert np.array_equal(Kg[:, :pos], kv[r][0][:, :pos]) and not Kg[:, pos + 1:].any()
 
 
+def test_70b_shaped_stack_two_tokens_free_running_and_teacher_forced():
+    """Six layers of the BASELINE config 3 stack (8 shards batched per launch, KV length 1024), two
+    tokens in a row.  Free-running: the device feeds itself and is compared with the oracle feeding
+    itself, layer by layer.  Teacher-forced: every device layer is also run from the oracle's input of
+    that layer, so a drift of the free-running comparison cannot hide behind accumulated error."""
+    m = configs.LLAMA2_70B_TP8
+    L, pos0, n_tok, max_seq = 6, 1024, 2, 1032
+    cfg = _cfg_of(m, max_seq)
+    oc = ocfg(cfg)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(7070)
+    shapes = synth.shard_tensor_shapes(m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local)
+    layers, host = [], []
+    for l in range(L):
+        shards, hs = [], []
+        for r in range(m.n_shards):
+            w = {}
+            for name, shp in shapes.items():
+                t = torch.randn(shp, generator=gen, device="cuda", dtype=torch.float32) * synth.WEIGHT_STD
+                if name.endswith("_norm"):
+                    t += 1.0
+                w[name] = t
+            K = torch.zeros((m.nkv_local, max_seq, m.head_dim), device="cuda")
+            V = torch.zeros_like(K)
+            K[:, :pos0] = torch.randn((m.nkv_local, pos0, m.head_dim), generator=gen, device="cuda")
+            V[:, :pos0] = torch.randn((m.nkv_local, pos0, m.head_dim), generator=gen, device="cuda")
+            hs.append(({k: v.cpu().numpy() for k, v in w.items()}, K.cpu().numpy(), V.cpu().numpy()))
+            sh = GpuShard.__new__(GpuShard)
+            sh.cfg = cfg; sh.w = w; sh.K = K; sh.V = V
+            sh.weights = B.make_weights(w); sh.kv = B.make_kv(K, V)
+            sh.partial = torch.empty(m.hidden, device="cuda")
+            sh.ws = torch.full((B.tpi_workspace_bytes(cfg, 1) // 4,), float("nan"), device="cuda")
+            shards.append(sh)
+        layers.append(shards); host.append(hs)
+    # a second set of device caches for the teacher-forced runs (they must not disturb the free-running ones)
+    tf_kv = [[(s.K.clone(), s.V.clone()) for s in shards] for shards in layers]
+    h_attn_t = torch.empty(m.hidden, device="cuda"); out_t = torch.empty(m.hidden, device="cuda")
+    tf_attn = torch.empty_like(h_attn_t); tf_out = torch.empty_like(out_t)
+    x0 = torch.randn(m.hidden, generator=gen, device="cuda")
+    worst_free = worst_tf = 0.0
+    for t in range(n_tok):
+        pos = pos0 + t
+        x_gpu = x0 + float(t)                       # a different input per token
+        x_orc = x_gpu.cpu().numpy()
+        for l in range(L):
+            shards = layers[l]
+            gpu_layer_decode(cfg, shards, pos, x_gpu, h_attn_t, out_t)
+            # teacher-forced: same layer, the oracle's input, separate caches
+            saved = [(s.K, s.V, s.kv) for s in shards]
+            for s, (Kc, Vc) in zip(shards, tf_kv[l]):
+                s.K, s.V, s.kv = Kc, Vc, B.make_kv(Kc, Vc)
+            gpu_layer_decode(cfg, shards, pos, torch.from_numpy(x_orc).cuda(), tf_attn, tf_out)
+            for s, (Kc, Vc, kvs) in zip(shards, saved):
+                s.K, s.V, s.kv = Kc, Vc, kvs
+            torch.cuda.synchronize()
+            wl = [h[0] for h in host[l]]; kv = [(h[1], h[2]) for h in host[l]]
+            h_ffn, h_attn, pa, pf = O.layer_decode(oc, wl, kv, pos, x_orc)
+            worst_tf = max(worst_tf, rel_err(tf_attn.cpu().numpy(), h_attn), rel_err(tf_out.cpu().numpy(), h_ffn))
+            worst_free = max(worst_free, rel_err(h_attn_t.cpu().numpy(), h_attn), rel_err(out_t.cpu().numpy(), h_ffn))
+            for r in range(m.n_shards):
+                assert rel_err(shards[r].K.cpu().numpy()[:, pos], kv[r][0][:, pos]) <= FP32_TOL
+            x_gpu = out_t.clone()
+            x_orc = h_ffn
+    print(f"70B-shaped stack, {L} layers x {n_tok} tokens: worst rel err teacher-forced {worst_tf:.2e}, "
+          f"free-running {worst_free:.2e}", flush=True)
+    assert worst_tf <= FP32_TOL
+    assert worst_free <= FP32_TOL
+
+
 # ----------------------------------------------------------------------------
 # Star reduce: bit-exact
 # ----------------------------------------------------------------------------
