@@ -147,3 +147,70 @@ def test_star_reduce_bf16_copy_is_round_to_nearest_even():
     ob4 = torch.empty(4, device="cuda", dtype=torch.bfloat16); o4 = torch.empty(4, device="cuda")
     B.tpi_star_reduce_bf16([t], None, o4, ob4); torch.cuda.synchronize()
     assert ob4.float().tolist() == [1.0, 1.0 + 2.0 ** -6, -1.0, 0.0]
+
+
+def test_prefill_three_layers_two_shards_teacher_forced_and_free_running():
+    """A prompt through a small stack the way bench.py chains the calls (attention phase -> reduce with the
+    bf16 copy -> FFN phase -> reduce), two shards.  The oracle follows the same interface: fp32 hidden state
+    as the shortcut, its bf16 rounding as the next block's input.  Every layer is checked teacher-forced
+    (device layer run from the oracle's input) and the whole chain free-running."""
+    h, nq, nkv, d, sl, n, N, L = 256, 2, 1, 64, 344, 70, 2, 3
+    rng = np.random.default_rng(21)
+    cfg = B.make_cfg(h, nq, nkv, d, sl, n, dtype=B.TPI_BF16)
+    oc = O.ShardCfg(h, nq, nkv, d, sl, n)
+    ws = torch.empty(B.tpi_workspace_bytes(cfg, n) // 4, device="cuda")
+    stack = []
+    for l in range(L):
+        row = []
+        for r in range(N):
+            w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+            wb = {k: (v if k.endswith("_norm") else synth.to_bf16_grid(v)) for k, v in w.items()}
+            wt = {k: (torch.from_numpy(v).cuda() if k.endswith("_norm") else _bf16_t(v)) for k, v in wb.items()}
+            row.append((wb, wt, B.make_weights(wt)))
+        stack.append(row)
+
+    def gpu_layer(l, x32_t):
+        x16 = x32_t.to(torch.bfloat16)
+        parts = [torch.empty((n, h), device="cuda") for _ in range(N)]
+        caches = []
+        for r in range(N):
+            Kt = torch.zeros((nkv, n, d), device="cuda", dtype=torch.bfloat16); Vt = torch.zeros_like(Kt)
+            caches.append((Kt, Vt))
+            B.tpi_shard_layer_prefill(cfg, stack[l][r][2], B.make_kv(Kt, Vt), 0, n, B.TPI_PHASE_ATTN, x16, parts[r], ws)
+        a32 = torch.empty_like(x32_t); a16 = torch.empty_like(x16)
+        B.tpi_star_reduce_bf16(parts, x32_t, a32, a16)
+        for r in range(N):
+            B.tpi_shard_layer_prefill(cfg, stack[l][r][2], None, 0, n, B.TPI_PHASE_FFN, a16, parts[r], ws)
+        o32 = torch.empty_like(x32_t); o16 = torch.empty_like(x16)
+        B.tpi_star_reduce_bf16(parts, a32, o32, o16)
+        torch.cuda.synchronize()
+        return a32, o32
+
+    def oracle_layer(l, x32):
+        x16 = synth.to_bf16_grid(x32)
+        pa = []
+        for r in range(N):
+            wb = stack[l][r][0]
+            K = np.zeros((nkv, n, d), np.float32); V = np.zeros_like(K)
+            pa.append(O.attn_block(oc, wb["attn_norm"], wb["w_qkv"], wb["w_o"], K, V, 0, x16))
+        a32 = O.reduce_f64(pa, x32).astype(np.float32)
+        a16 = synth.to_bf16_grid(a32)
+        pf = [O.ffn_block(oc, stack[l][r][0]["ffn_norm"], stack[l][r][0]["w_gate"], stack[l][r][0]["w_up"],
+                          stack[l][r][0]["w_down"], a16) for r in range(N)]
+        return a32, O.reduce_f64(pf, a32).astype(np.float32)
+
+    x0 = synth.to_bf16_grid(rng.standard_normal((n, h)).astype(np.float32))
+    x_orc, x_gpu = x0, torch.from_numpy(x0).cuda()
+    worst_tf = worst_free = 0.0
+    for l in range(L):
+        ra, ro = oracle_layer(l, x_orc)
+        ta, to = gpu_layer(l, torch.from_numpy(x_orc).cuda())                  # teacher-forced
+        worst_tf = max(worst_tf, rel_err(ta.cpu().numpy(), ra), rel_err(to.cpu().numpy(), ro))
+        fa, fo = gpu_layer(l, x_gpu)                                           # free-running
+        worst_free = max(worst_free, rel_err(fa.cpu().numpy(), ra), rel_err(fo.cpu().numpy(), ro))
+        x_orc, x_gpu = ro, fo
+    print(f"prefill stack {L} layers x {N} shards: worst rel err teacher-forced {worst_tf:.2e}, free-running {worst_free:.2e}",
+          flush=True)
+    assert worst_tf <= BF16_TOL
+    assert worst_free <= BF16_TOL
+
