@@ -41,9 +41,9 @@ struct DecodeDims {
 // is in registers, the peers' partials are in memory).  out[i] = sum in rank order, then + residual.
 struct FusedReduce {
     int n = 0, rank = 0;                  // n == 0: no folding, the stage stores its partial
-    const float *peer[kMaxBatchShards] = {};   // partial vectors of the ranks; entry `rank` is not read
     const float *residual = nullptr;
     float *out = nullptr;
+    const float *peer[kMaxBatchShards] = {};   // partial vectors of the ranks; entry `rank` is not read
 };
 
 struct DecodeArgs : DecodeDims {

@@ -43,11 +43,12 @@ __global__ __launch_bounds__(kBlock) void k_attn(DecodeArgs a)
     stage_attn<GT, EPL>(a, a.s[blockIdx.z], blockIdx.x, g, ht, smem);
 }
 
-template <int ROWS, int KCH, int UB, bool FOLD>
+// FOLD: 0 plain; 8 / 16: the star reduce folded in, with that many rank slots compiled in
+template <int ROWS, int KCH, int UB, int FOLD>
 __global__ __launch_bounds__(kBlock) void k_oproj(DecodeArgs a)
 {
     __shared__ float red[ROWS * kWavesPerBlock];
-    stage_oproj<ROWS, KCH, UB, FOLD>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
+    stage_oproj<ROWS, KCH, UB, (FOLD > 0), (FOLD > 0 ? FOLD : 8)>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
 }
 
 template <int COLS, int KCH, int UB>
@@ -57,11 +58,11 @@ __global__ __launch_bounds__(kBlock) void k_gate_up(DecodeArgs a)
     stage_gate_up<COLS, KCH, UB>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red);
 }
 
-template <int ROWS, int KCH, int UB, bool FOLD>
+template <int ROWS, int KCH, int UB, int FOLD>
 __global__ __launch_bounds__(kBlock) void k_down(DecodeArgs a)
 {
     __shared__ float red[ROWS * kWavesPerBlock];
-    stage_down<ROWS, KCH, UB, FOLD>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
+    stage_down<ROWS, KCH, UB, (FOLD > 0), (FOLD > 0 ? FOLD : 8)>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
 }
 
 // ---------------------------------------------------------------------------
@@ -152,8 +153,9 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         TPI_KCH_SWITCH(a.nq * a.d, {
             constexpr int ROWS = WIDE ? 8 : 4;
             int gx = std::max(balanced_grid(cdiv(a.h, ROWS)), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
-            if (a.rf.n > 0) hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, true>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
-            else hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, false>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            if (a.rf.n > 8) hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, 16>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            else if (a.rf.n > 0) hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, 8>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            else hipLaunchKernelGGL((k_oproj<ROWS, KCH, UB, 0>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
         return hipGetLastError();
     }
@@ -176,8 +178,9 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
         TPI_KCH_SWITCH(a.sl, {
             constexpr int ROWS = WIDE ? 8 : 4;
             int gx = std::max(balanced_grid(cdiv(a.h, ROWS)), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
-            if (a.rf.n > 0) hipLaunchKernelGGL((k_down<ROWS, KCH, UB, true>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
-            else hipLaunchKernelGGL((k_down<ROWS, KCH, UB, false>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            if (a.rf.n > 8) hipLaunchKernelGGL((k_down<ROWS, KCH, UB, 16>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            else if (a.rf.n > 0) hipLaunchKernelGGL((k_down<ROWS, KCH, UB, 8>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
+            else hipLaunchKernelGGL((k_down<ROWS, KCH, UB, 0>), dim3(gx, n_shards), dim3(kBlock), 0, st, a);
         })
         return hipGetLastError();
     }

@@ -62,20 +62,23 @@ __device__ __forceinline__ void emit_row(const ShardView &s, const FusedReduce &
 }
 
 // The same in two halves, for the row-parallel stages: the peers' values and the shortcut of the row a
-// thread will finish are requested when the kernel starts -- ahead of the weight stream in the in-order
-// memory pipe, so they cost no round trip at the end -- and summed once the shard's own value exists.
+// thread will finish are requested early -- long before they are needed, so they cost no round trip at
+// the end -- and summed once the shard's own value exists.  NP: the number of rank slots compiled in
+// (8 or 16); with up to 8 ranks the table of peer pointers is one read of the kernel arguments.
+template <int NP>
 struct PeerRow {
-    float v[kMaxBatchShards];
+    float v[NP];
     float res;
 };
 
 // Every load is unconditional -- slots without a peer read `dummy[row]` (any readable array of at least
 // row + 1 floats) and are ignored later: a load under a branch makes the compiler wait for all earlier
 // loads at the join, which would turn these requests into a chain of round trips.
-__device__ __forceinline__ void fetch_peers(const FusedReduce &rf, int row, const float *dummy, PeerRow &p)
+template <int NP>
+__device__ __forceinline__ void fetch_peers(const FusedReduce &rf, int row, const float *dummy, PeerRow<NP> &p)
 {
 #pragma unroll
-    for (int i = 0; i < kMaxBatchShards; ++i) {
+    for (int i = 0; i < NP; ++i) {
         const float *src = (i < rf.n && i != rf.rank) ? rf.peer[i] : dummy;
         p.v[i] = src[row];
     }
@@ -83,11 +86,12 @@ __device__ __forceinline__ void fetch_peers(const FusedReduce &rf, int row, cons
     p.res = rs[row];
 }
 
-__device__ __forceinline__ void emit_row(const FusedReduce &rf, int row, float y, const PeerRow &p)
+template <int NP>
+__device__ __forceinline__ void emit_row(const FusedReduce &rf, int row, float y, const PeerRow<NP> &p)
 {
     float acc = 0.f;
 #pragma unroll
-    for (int i = 0; i < kMaxBatchShards; ++i) {
+    for (int i = 0; i < NP; ++i) {
         if (i < rf.n) {
             float t = (i == rf.rank) ? y : p.v[i];
             acc = (i == 0) ? t : acc + t;
@@ -169,7 +173,7 @@ __device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &
 }
 
 // Stage 3: a unit is ROWS rows of W_o; the input is the merged attention output.
-template <int ROWS, int KCH, int UB, bool FOLD>
+template <int ROWS, int KCH, int UB, bool FOLD, int NP = kMaxBatchShards>
 __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
                                             const FusedReduce &rf)
 {
@@ -189,7 +193,7 @@ __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView
     // long before they are needed.
     constexpr bool fold = FOLD;      // compile-time: the plain stage carries none of the folding code
     int my_row = -1;
-    PeerRow peers;
+    PeerRow<NP> peers;
     if constexpr (fold) {
         if (vwg < n_units) {
             const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
@@ -258,7 +262,7 @@ __device__ __forceinline__ void stage_gate_up(const DecodeDims &a, const ShardVi
 }
 
 // Stage 5: a unit is ROWS rows of W_down.
-template <int ROWS, int KCH, int UB, bool FOLD>
+template <int ROWS, int KCH, int UB, bool FOLD, int NP = kMaxBatchShards>
 __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
                                            const FusedReduce &rf)
 {
@@ -274,7 +278,7 @@ __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView 
     // see stage_oproj
     constexpr bool fold = FOLD;
     int my_row = -1;
-    PeerRow peers;
+    PeerRow<NP> peers;
     if constexpr (fold) {
         if (vwg < n_units) {
             const int my_rows = ((n_units - vwg + nvwg - 1) / nvwg) * ROWS;
