@@ -1,8 +1,10 @@
 /*
  * libtpi -- MI355X (gfx950) hot path of TPI-LLM tensor-parallel inference
  * (arxiv 2410.00531): one device's shard of a Llama-style decoder layer, the
- * star all-reduce sum of the N shards' partial outputs, and a sliding window
- * of layer shards streamed from pinned host memory into HBM.
+ * star all-reduce sum of the N shards' partial outputs, a sliding window of
+ * layer shards (or attention / FFN blocks) streamed from pinned host memory
+ * into HBM, the bf16 prefill of the same shard, and the master's embedding,
+ * task head and token choice.
  *
  * Conventions for every entry point
  *   - C ABI, plain pointers and sizes.  A pointer is a DEVICE pointer unless
@@ -12,13 +14,14 @@
  *     never synchronise, allocate or free.
  *   - The caller owns every buffer (weights, KV cache, activations,
  *     workspace, pinned host blobs, window slots).  The library owns only
- *     tpi_window objects.
+ *     tpi_window and tpi_decoder objects.
  *   - Return value: TPI_OK (0) or a negative tpi_status.  Argument errors are
  *     detected before anything is queued; tpi_last_error() returns a
  *     thread-local description of the last failure.
  *   - Weight matrices are row-major [out][in], so y = W x reads rows of W.
  *   - Alignment: every device pointer 16-byte aligned; hidden, ffn_local and
- *     head_dim multiples of 4 (TPI_EUNSUPPORTED otherwise).
+ *     head_dim multiples of 4 for fp32 shards, of 8 for bf16 shards
+ *     (TPI_EUNSUPPORTED otherwise).
  */
 #ifndef TPI_H
 #define TPI_H

@@ -14,7 +14,7 @@ pytestmark = [
     pytest.mark.gpu,
     pytest.mark.skip(reason="the whole-token kernel is switched off (tpi_decoder_create returns TPI_EUNSUPPORTED): "
                             "one run of the 8B-shaped case stopped at a grid barrier until its bounded wait gave up, "
-                            "and the cause has not been shown yet; see DESIGN.md"),
+                            "and the cause has not been shown yet"),
 ]
 
 
