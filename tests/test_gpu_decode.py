@@ -77,6 +77,35 @@ def test_ragged_shapes(h, nq, nkv, d, sl):
     check_ffn_phase(cfg, w, x)
 
 
+def _random_decode_shapes(n, seed):
+    """Seeded random shard shapes inside the documented limits: hidden and FFN width multiples of 4, head
+    sizes even multiples of 4 up to 256, any group size, positions anywhere in the cache."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([4, 8, 12, 16, 24, 32, 40, 64, 80, 96, 128, 160, 192, 256]))
+        nkv = int(rng.integers(1, 4))
+        G = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 9, 16]))
+        if G * nkv * d > 2048:
+            G = max(1, 2048 // (nkv * d))
+        h = 4 * int(rng.integers(1, 600))
+        sl = 4 * int(rng.integers(1, 700))
+        max_seq = int(rng.integers(1, 700))
+        pos = int(rng.integers(0, max_seq))
+        out.append((h, G * nkv, nkv, d, sl, pos, max_seq))
+    return out
+
+
+@pytest.mark.parametrize("h,nq,nkv,d,sl,pos,max_seq", _random_decode_shapes(24, 2024))
+def test_random_shapes_both_phases(h, nq, nkv, d, sl, pos, max_seq):
+    rng = np.random.default_rng(h * 7 + sl + pos)
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq)
+    w, K, V = random_shard_np(rng, cfg, pos)
+    x = rng.standard_normal(h).astype(np.float32)
+    check_attn_phase(cfg, w, K, V, pos, x)
+    check_ffn_phase(cfg, w, x)
+
+
 @pytest.mark.parametrize("pos,max_seq", [
     (0, 1), (0, 8), (1, 8), (63, 64), (64, 65), (65, 130), (127, 128), (2047, 2048), (2048, 2100),
     (2111, 2112), (4500, 4501),

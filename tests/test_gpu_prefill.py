@@ -79,6 +79,27 @@ def test_prefill_parity_small_shapes(h, nq, nkv, d, sl, n, pos0):
     _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + 3, seed=h + n + pos0, attn_scale=4.0)
 
 
+def _random_prefill_shapes(n, seed):
+    """Seeded random shapes inside the documented limits of the bf16 path: every size a multiple of 8."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        d = int(rng.choice([8, 16, 32, 48, 64, 96, 128]))
+        nkv = int(rng.integers(1, 3))
+        G = int(rng.choice([1, 2, 3, 4, 8]))
+        h = 8 * int(rng.integers(2, 80))
+        sl = 8 * int(rng.integers(1, 90))
+        n_tok = int(rng.integers(1, 200))
+        pos0 = int(rng.choice([0, 0, int(rng.integers(0, 70))]))
+        out.append((h, G * nkv, nkv, d, sl, n_tok, pos0))
+    return out
+
+
+@pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0", _random_prefill_shapes(12, 512))
+def test_prefill_random_shapes(h, nq, nkv, d, sl, n, pos0):
+    _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + int(n % 3), seed=h + n + pos0 + d, attn_scale=4.0)
+
+
 def test_prefill_single_token_and_last_slot():
     _run_prefill_case(256, 2, 2, 64, 344, 1, 0, 1, seed=1)
     _run_prefill_case(256, 2, 2, 64, 344, 1, 15, 16, seed=2)
