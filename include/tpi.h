@@ -257,6 +257,36 @@ typedef struct tpi_window_slots {
 
 int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_window_block *blocks,
                              int32_t n_classes, const tpi_window_slots *classes);
+
+/*
+ * The paper's own source tier: the weights stay in files ("dynamically loading
+ * and unloading model weights", Sec. 3.3; the scheduler "operates on a daemon
+ * thread").  Blocks are byte ranges of files; the window owns a loader thread
+ * and n_staging pinned staging buffers of the largest block's size.  prefetch
+ * only queues the request and returns; the loader reads the block into the
+ * next staging buffer (pread) and forwards it to its HBM slot on the window's
+ * copy stream, strictly in request order.  acquire blocks the CALLING THREAD
+ * until the loader has queued that copy (not until it has finished: the
+ * compute stream waits for that, as with the other windows), so a prefetch
+ * issued well ahead costs the caller nothing.  Slot classes, retention,
+ * states and errors are those of tpi_window_create_blocks.  Files are read
+ * through the page cache; they must not change while the window exists.
+ * tpi_window_read_stats: time the loader has spent reading files so far.
+ * TPI_EINVAL also for a file that cannot be opened; a read error or a short
+ * file surfaces as TPI_ERUNTIME at the next prefetch / acquire / copy_stats.
+ */
+typedef struct tpi_window_file_block {
+    const char *path;     /* host string, copied */
+    uint64_t offset;      /* byte offset of the block in the file */
+    size_t bytes;
+    int32_t slot_class;
+    int32_t retained;
+    void *resident;
+} tpi_window_file_block;
+
+int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window_file_block *blocks,
+                            int32_t n_classes, const tpi_window_slots *classes, int32_t n_staging);
+int tpi_window_read_stats(tpi_window *w, double *read_ms);
 /* Total time (ms) the copy stream spent in copies between the first prefetch
  * and the last one completed so far, and the bytes they moved; synchronises
  * the copy stream.  Either output may be NULL. */

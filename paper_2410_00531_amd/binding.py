@@ -26,7 +26,7 @@ EXPORTED = (
     "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode",
     "tpi_shard_layer_decode_reduce",
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create",
-    "tpi_window_create_blocks", "tpi_window_prefetch",
+    "tpi_window_create_blocks", "tpi_window_create_files", "tpi_window_read_stats", "tpi_window_prefetch",
     "tpi_embed_token", "tpi_lm_head", "tpi_next_token",
     "tpi_window_acquire", "tpi_window_release", "tpi_window_destroy", "tpi_window_copy_stats",
     "tpi_last_error", "tpi_abi_version", "tpi_prof_enable", "tpi_prof_read",
@@ -61,6 +61,11 @@ class tpi_kv_layer(C.Structure):
 
 class tpi_window_block(C.Structure):
     _fields_ = [("host", C.c_void_p), ("bytes", C.c_size_t), ("slot_class", C.c_int32),
+                ("retained", C.c_int32), ("resident", C.c_void_p)]
+
+
+class tpi_window_file_block(C.Structure):
+    _fields_ = [("path", C.c_char_p), ("offset", C.c_uint64), ("bytes", C.c_size_t), ("slot_class", C.c_int32),
                 ("retained", C.c_int32), ("resident", C.c_void_p)]
 
 
@@ -113,6 +118,11 @@ def lib() -> C.CDLL:
         l.tpi_window_create_blocks.restype = C.c_int
         l.tpi_window_create_blocks.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.POINTER(tpi_window_block),
                                                C.c_int32, C.POINTER(tpi_window_slots)]
+        l.tpi_window_create_files.restype = C.c_int
+        l.tpi_window_create_files.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.POINTER(tpi_window_file_block),
+                                              C.c_int32, C.POINTER(tpi_window_slots), C.c_int32]
+        l.tpi_window_read_stats.restype = C.c_int
+        l.tpi_window_read_stats.argtypes = [C.c_void_p, C.POINTER(C.c_double)]
         for name in ("tpi_window_prefetch",):
             getattr(l, name).restype = C.c_int
             getattr(l, name).argtypes = [C.c_void_p, C.c_int32]
@@ -373,6 +383,28 @@ class Window:
             carr[i] = tpi_window_slots(_ptr(base), slot_bytes, n_slots)
         _check(lib().tpi_window_create_blocks(C.byref(self._h), len(blocks), barr, len(classes), carr))
         return self
+
+    @classmethod
+    def from_files(cls, blocks, classes, n_staging: int = 2) -> "Window":
+        """tpi_window_create_files.  blocks: sequence of (path, offset, nbytes, slot_class, resident);
+        classes as in from_blocks."""
+        self = cls.__new__(cls)
+        self._h = C.c_void_p()
+        self._keep = (list(blocks), list(classes))
+        barr = (tpi_window_file_block * len(blocks))()
+        for i, (path, offset, nbytes, slot_class, resident) in enumerate(blocks):
+            barr[i] = tpi_window_file_block(os.fsencode(path), offset, nbytes, slot_class,
+                                            1 if resident is not None else 0, _ptr(resident))
+        carr = (tpi_window_slots * len(classes))()
+        for i, (base, slot_bytes, n_slots) in enumerate(classes):
+            carr[i] = tpi_window_slots(_ptr(base), slot_bytes, n_slots)
+        _check(lib().tpi_window_create_files(C.byref(self._h), len(blocks), barr, len(classes), carr, n_staging))
+        return self
+
+    def read_ms(self) -> float:
+        ms = C.c_double()
+        _check(lib().tpi_window_read_stats(self._h, C.byref(ms)))
+        return ms.value
 
     def prefetch(self, layer: int) -> None:
         _check(lib().tpi_window_prefetch(self._h, layer))

@@ -8,7 +8,17 @@
 // home of its own, is copied once and never evicted.
 #include <hip/hip_runtime.h>
 
+#include <fcntl.h>
+#include <unistd.h>
+
+#include <cerrno>
+#include <condition_variable>
+#include <cstring>
+#include <deque>
+#include <mutex>
 #include <new>
+#include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/tpi.h"
@@ -44,7 +54,9 @@ struct Ring {
 };
 
 struct Block {
-    const void *host = nullptr;
+    const void *host = nullptr;   // pinned host memory, or null with the file tier
+    int fd = -1;                  // file tier: open file and offset of the block
+    uint64_t file_offset = 0;
     size_t bytes = 0;
     int cls = 0;
     char *resident = nullptr;     // non-null: retained block
@@ -55,6 +67,15 @@ struct Block {
 
 }  // namespace
 
+// One request to the loader thread: read block -> staging buffer -> dst.
+struct LoadRequest {
+    int block = -1;
+    void *dst = nullptr;
+    hipEvent_t after = nullptr;   // the copy must wait for this event (previous tenant released), may be null
+    hipEvent_t ready = nullptr;   // recorded on the copy stream after the copy
+    uint64_t seq = 0;
+};
+
 struct tpi_window {
     std::vector<Block> blocks;
     std::vector<Ring> rings;
@@ -62,6 +83,25 @@ struct tpi_window {
     hipEvent_t first_begin = nullptr, last_done = nullptr;   // timing span of the copies
     bool any_copy = false;
     uint64_t bytes_copied = 0;
+
+    // file tier
+    bool file_tier = false;
+    int device = 0;
+    std::vector<int> fds;                    // distinct files, closed at destroy
+    std::vector<void *> staging;             // pinned buffers, owned by the window
+    std::vector<hipEvent_t> staging_done;    // the staging buffer's last copy has left it
+    std::vector<char> staging_used;
+    size_t staging_bytes = 0;
+    std::thread loader;
+    std::mutex mu;
+    std::condition_variable cv_req, cv_done;
+    std::deque<LoadRequest> queue;
+    uint64_t n_requested = 0, n_issued = 0;  // requests handed to / finished by the loader
+    std::vector<uint64_t> issued_seq;        // per block: sequence number of its latest request
+    bool stop = false;
+    bool loader_failed = false;
+    std::string loader_error;
+    double read_seconds = 0.0;               // time the loader spent in pread
 };
 
 using tpi::fail;
@@ -76,6 +116,12 @@ namespace {
 
 void destroy_objects(tpi_window *w)
 {
+    for (auto e : w->staging_done)
+        if (e) (void)hipEventDestroy(e);
+    for (auto p : w->staging)
+        if (p) (void)hipHostFree(p);
+    for (int fd : w->fds)
+        if (fd >= 0) ::close(fd);
     for (auto &r : w->rings)
         for (auto &s : r.slots) {
             if (s.ready) (void)hipEventDestroy(s.ready);
@@ -88,8 +134,23 @@ void destroy_objects(tpi_window *w)
     if (w->copy) (void)hipStreamDestroy(w->copy);
 }
 
-int queue_copy(tpi_window *w, void *dst, const Block &b, hipEvent_t ready)
+// `after`: event the copy has to wait for (the slot's previous tenant released), or null.
+int queue_copy(tpi_window *w, int block, void *dst, hipEvent_t after, hipEvent_t ready)
 {
+    const Block &b = w->blocks[block];
+    if (w->file_tier) {
+        // hand the request to the loader thread; acquire() waits until it has been carried out
+        std::lock_guard<std::mutex> lk(w->mu);
+        if (w->loader_failed) return fail(TPI_ERUNTIME, "loader thread: %s", w->loader_error.c_str());
+        LoadRequest rq;
+        rq.block = block; rq.dst = dst; rq.after = after; rq.ready = ready; rq.seq = ++w->n_requested;
+        w->issued_seq[block] = rq.seq;
+        w->queue.push_back(rq);
+        w->bytes_copied += b.bytes;
+        w->cv_req.notify_one();
+        return TPI_OK;
+    }
+    if (after) TPI_HIP(hipStreamWaitEvent(w->copy, after, 0));
     if (!w->any_copy) TPI_HIP(hipEventRecord(w->first_begin, w->copy));
     TPI_HIP(hipMemcpyAsync(dst, b.host, b.bytes, hipMemcpyHostToDevice, w->copy));
     TPI_HIP(hipEventRecord(ready, w->copy));
@@ -99,12 +160,98 @@ int queue_copy(tpi_window *w, void *dst, const Block &b, hipEvent_t ready)
     return TPI_OK;
 }
 
+// File tier: block until the loader has carried out the latest request for `block` (its copy is queued and
+// its ready event recorded), so that the caller may make a stream wait for that event.
+int wait_issued(tpi_window *w, int block)
+{
+    if (!w->file_tier) return TPI_OK;
+    std::unique_lock<std::mutex> lk(w->mu);
+    const uint64_t seq = w->issued_seq[block];
+    w->cv_done.wait(lk, [&] { return w->n_issued >= seq || w->loader_failed; });
+    if (w->loader_failed) return fail(TPI_ERUNTIME, "loader thread: %s", w->loader_error.c_str());
+    return TPI_OK;
+}
+
+void loader_fail(tpi_window *w, const std::string &msg)
+{
+    std::lock_guard<std::mutex> lk(w->mu);
+    w->loader_failed = true;
+    w->loader_error = msg;
+    w->cv_done.notify_all();
+}
+
+// The scheduler's daemon thread: requests are carried out strictly in order.
+void loader_main(tpi_window *w)
+{
+    if (hipSetDevice(w->device) != hipSuccess) { loader_fail(w, "hipSetDevice failed"); return; }
+    uint64_t k = 0;
+    for (;;) {
+        LoadRequest rq;
+        {
+            std::unique_lock<std::mutex> lk(w->mu);
+            w->cv_req.wait(lk, [&] { return w->stop || !w->queue.empty(); });
+            if (w->queue.empty()) return;          // stop requested and nothing left to do
+            rq = w->queue.front();
+            w->queue.pop_front();
+        }
+        const Block &b = w->blocks[rq.block];
+        const int si = (int)(k % w->staging.size());
+        k += 1;
+        hipError_t e = hipSuccess;
+        if (w->staging_used[si]) e = hipEventSynchronize(w->staging_done[si]);   // its previous copy has left it
+        if (e != hipSuccess) { loader_fail(w, std::string("hipEventSynchronize: ") + hipGetErrorString(e)); return; }
+        // read the block from its file
+        timespec t0, t1;
+        clock_gettime(CLOCK_MONOTONIC, &t0);
+        size_t got = 0;
+        char *dst = static_cast<char *>(w->staging[si]);
+        while (got < b.bytes) {
+            ssize_t r = ::pread(b.fd, dst + got, b.bytes - got, (off_t)(b.file_offset + got));
+            if (r < 0 && errno == EINTR) continue;
+            if (r <= 0) {
+                loader_fail(w, r == 0 ? "block " + std::to_string(rq.block) + ": file ends inside the block"
+                                      : "block " + std::to_string(rq.block) + ": pread: " + std::strerror(errno));
+                return;
+            }
+            got += (size_t)r;
+        }
+        clock_gettime(CLOCK_MONOTONIC, &t1);
+        if (rq.after) e = hipStreamWaitEvent(w->copy, rq.after, 0);
+        if (e == hipSuccess && !w->any_copy) e = hipEventRecord(w->first_begin, w->copy);
+        if (e == hipSuccess) e = hipMemcpyAsync(rq.dst, w->staging[si], b.bytes, hipMemcpyHostToDevice, w->copy);
+        if (e == hipSuccess) e = hipEventRecord(rq.ready, w->copy);
+        if (e == hipSuccess) e = hipEventRecord(w->staging_done[si], w->copy);
+        if (e == hipSuccess) e = hipEventRecord(w->last_done, w->copy);
+        if (e != hipSuccess) { loader_fail(w, std::string("copy of a block: ") + hipGetErrorString(e)); return; }
+        w->staging_used[si] = 1;
+        {
+            std::lock_guard<std::mutex> lk(w->mu);
+            w->any_copy = true;
+            w->n_issued = rq.seq;
+            w->read_seconds += (double)(t1.tv_sec - t0.tv_sec) + 1e-9 * (double)(t1.tv_nsec - t0.tv_nsec);
+            w->cv_done.notify_all();
+        }
+    }
+}
+
+// stops the loader (after it has carried out everything queued) and joins it
+void stop_loader(tpi_window *w)
+{
+    if (!w->file_tier || !w->loader.joinable()) return;
+    {
+        std::lock_guard<std::mutex> lk(w->mu);
+        w->stop = true;
+        w->cv_req.notify_all();
+    }
+    w->loader.join();
+}
+
 }  // namespace
 
 extern "C" {
 
-int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_window_block *blocks, int32_t n_classes,
-                             const tpi_window_slots *classes)
+static int create_common(tpi_window **out, int32_t n_blocks, const tpi_window_block *blocks, int32_t n_classes,
+                         const tpi_window_slots *classes, bool need_host)
 {
     if (!out) return fail(TPI_EINVAL, "out is null");
     *out = nullptr;
@@ -115,7 +262,7 @@ int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_windo
             return fail(TPI_EINVAL, "slot class %d: null or empty slots", c);
     for (int i = 0; i < n_blocks; ++i) {
         const tpi_window_block &b = blocks[i];
-        if (!b.host || b.bytes == 0) return fail(TPI_EINVAL, "block %d: null or empty host memory", i);
+        if ((need_host && !b.host) || b.bytes == 0) return fail(TPI_EINVAL, "block %d: null or empty host memory", i);
         if (b.retained) {
             if (!b.resident) return fail(TPI_EINVAL, "block %d is retained but has no resident device memory", i);
         } else {
@@ -162,6 +309,95 @@ int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_windo
     return TPI_OK;
 }
 
+int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_window_block *blocks, int32_t n_classes,
+                             const tpi_window_slots *classes)
+{
+    return create_common(out, n_blocks, blocks, n_classes, classes, true);
+}
+
+int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window_file_block *blocks, int32_t n_classes,
+                            const tpi_window_slots *classes, int32_t n_staging)
+{
+    if (!out) return fail(TPI_EINVAL, "out is null");
+    *out = nullptr;
+    if (n_blocks < 1 || !blocks) return fail(TPI_EINVAL, "null or empty block list");
+    if (n_staging < 1) return fail(TPI_EINVAL, "n_staging %d < 1", n_staging);
+    std::vector<tpi_window_block> plain(n_blocks);
+    size_t largest = 0;
+    for (int i = 0; i < n_blocks; ++i) {
+        if (!blocks[i].path) return fail(TPI_EINVAL, "block %d: path is null", i);
+        plain[i] = tpi_window_block{nullptr, blocks[i].bytes, blocks[i].slot_class, blocks[i].retained, blocks[i].resident};
+        if (blocks[i].bytes > largest) largest = blocks[i].bytes;
+    }
+    // open every distinct file once (before anything is created on the device)
+    std::vector<std::string> paths;
+    std::vector<int> fds, fd_of(n_blocks, -1);
+    auto close_all = [&] {
+        for (int fd : fds) ::close(fd);
+    };
+    for (int i = 0; i < n_blocks; ++i) {
+        int at = -1;
+        for (size_t k = 0; k < paths.size(); ++k)
+            if (paths[k] == blocks[i].path) at = (int)k;
+        if (at < 0) {
+            int fd = ::open(blocks[i].path, O_RDONLY | O_CLOEXEC);
+            if (fd < 0) {
+                int rc = fail(TPI_EINVAL, "block %d: cannot open %s: %s", i, blocks[i].path, std::strerror(errno));
+                close_all();
+                return rc;
+            }
+            paths.push_back(blocks[i].path);
+            fds.push_back(fd);
+            at = (int)paths.size() - 1;
+        }
+        fd_of[i] = fds[at];
+    }
+    tpi_window *w = nullptr;
+    int rc = create_common(&w, n_blocks, plain.data(), n_classes, classes, false);
+    if (rc != TPI_OK) {
+        close_all();
+        return rc;
+    }
+    w->fds = fds;                                   // the window closes them from here on
+    for (int i = 0; i < n_blocks; ++i) {
+        w->blocks[i].fd = fd_of[i];
+        w->blocks[i].file_offset = blocks[i].offset;
+    }
+    auto bail = [&](int code) {
+        destroy_objects(w);
+        delete w;
+        return code;
+    };
+    if (hipGetDevice(&w->device) != hipSuccess) return bail(fail(TPI_ERUNTIME, "hipGetDevice failed"));
+    w->staging_bytes = largest;
+    w->staging.assign(n_staging, nullptr);
+    w->staging_done.assign(n_staging, nullptr);
+    w->staging_used.assign(n_staging, 0);
+    w->issued_seq.assign(n_blocks, 0);
+    for (int k = 0; k < n_staging; ++k) {
+        hipError_t e = hipHostMalloc(&w->staging[k], largest, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&w->staging_done[k], hipEventDisableTiming);
+        if (e != hipSuccess) return bail(fail(TPI_ERUNTIME, "staging buffers: %s", hipGetErrorString(e)));
+    }
+    w->file_tier = true;
+    try {
+        w->loader = std::thread(loader_main, w);
+    } catch (...) {
+        w->file_tier = false;
+        return bail(fail(TPI_ERUNTIME, "cannot start the loader thread"));
+    }
+    *out = w;
+    return TPI_OK;
+}
+
+int tpi_window_read_stats(tpi_window *w, double *read_ms)
+{
+    if (!w || !read_ms) return fail(TPI_EINVAL, "null argument");
+    std::lock_guard<std::mutex> lk(w->mu);
+    *read_ms = w->read_seconds * 1e3;
+    return TPI_OK;
+}
+
 int tpi_window_create(tpi_window **out, int32_t n_layers, int32_t window_layers, size_t layer_bytes,
                       const void *const *host_layer_blobs, void *device_slots)
 {
@@ -187,7 +423,7 @@ int tpi_window_prefetch(tpi_window *w, int32_t layer)
     if (b.resident) {
         // retained: the first prefetch brings it in for good, later ones find it there
         if (b.loaded) return TPI_OK;
-        int rc = queue_copy(w, b.resident, b, b.ready);
+        int rc = queue_copy(w, layer, b.resident, nullptr, b.ready);
         if (rc != TPI_OK) return rc;
         b.loaded = true;
         return TPI_OK;
@@ -199,8 +435,7 @@ int tpi_window_prefetch(tpi_window *w, int32_t layer)
         return fail(TPI_ESTATE, "prefetch of block %d: the window is full, slot %d of class %d still holds block %d (%s)",
                     layer, si, b.cls, s.block, s.state == kAcquired ? "acquired, not released" : "prefetched, not yet used");
     // the previous tenant's readers must have finished before the copy lands
-    if (s.state == kReleased) TPI_HIP(hipStreamWaitEvent(w->copy, s.freed, 0));
-    int rc = queue_copy(w, r.base + (size_t)si * r.slot_bytes, b, s.ready);
+    int rc = queue_copy(w, layer, r.base + (size_t)si * r.slot_bytes, s.state == kReleased ? s.freed : nullptr, s.ready);
     if (rc != TPI_OK) return rc;
     r.n_prefetch += 1;
     s.block = layer;
@@ -216,6 +451,7 @@ int tpi_window_acquire(tpi_window *w, int32_t layer, void *compute_stream, const
     Block &b = w->blocks[layer];
     if (b.resident) {
         if (!b.loaded) return fail(TPI_ESTATE, "acquire of retained block %d: it was never prefetched", layer);
+        if (int rc = wait_issued(w, layer)) return rc;
         TPI_HIP(hipStreamWaitEvent((hipStream_t)compute_stream, b.ready, 0));
         b.acquired += 1;
         *dev_blob = b.resident;
@@ -225,6 +461,7 @@ int tpi_window_acquire(tpi_window *w, int32_t layer, void *compute_stream, const
     const int si = r.find(layer, kPrefetched);
     if (si < 0) return fail(TPI_ESTATE, "acquire of block %d: no prefetched copy of it is in the window", layer);
     Slot &s = r.slots[si];
+    if (int rc = wait_issued(w, layer)) return rc;
     TPI_HIP(hipStreamWaitEvent((hipStream_t)compute_stream, s.ready, 0));
     s.state = kAcquired;
     *dev_blob = r.base + (size_t)si * r.slot_bytes;
@@ -254,6 +491,12 @@ int tpi_window_release(tpi_window *w, int32_t layer, void *compute_stream)
 int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes)
 {
     if (!w) return fail(TPI_EINVAL, "window is null");
+    if (w->file_tier) {
+        // everything requested so far must have been handed to the copy stream
+        std::unique_lock<std::mutex> lk(w->mu);
+        w->cv_done.wait(lk, [&] { return w->n_issued >= w->n_requested || w->loader_failed; });
+        if (w->loader_failed) return fail(TPI_ERUNTIME, "loader thread: %s", w->loader_error.c_str());
+    }
     if (bytes) *bytes = w->bytes_copied;
     if (copy_ms) {
         *copy_ms = 0.0;
@@ -270,6 +513,7 @@ int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes)
 int tpi_window_destroy(tpi_window *w)
 {
     if (!w) return fail(TPI_EINVAL, "window is null");
+    stop_loader(w);
     hipError_t e = hipStreamSynchronize(w->copy);
     destroy_objects(w);
     delete w;

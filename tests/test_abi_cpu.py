@@ -34,6 +34,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(B.tpi_kv_layer) == 16
     assert C.sizeof(B.tpi_window_block) == 32
     assert C.sizeof(B.tpi_window_slots) == 24
+    assert C.sizeof(B.tpi_window_file_block) == 40
 
 
 def _w():
@@ -129,6 +130,17 @@ def test_window_argument_errors_without_a_device():
     assert cb(C.byref(h), 1, mk(blk(retained=1)), 1, one_class) == B.TPI_EINVAL         # retained, no home
     assert cb(C.byref(h), 1, mk(blk()), 1, (B.tpi_window_slots * 1)(B.tpi_window_slots(FAKE, 16, 0))) == B.TPI_EINVAL
     assert cb(C.byref(h), 1, mk(blk()), 1, (B.tpi_window_slots * 1)(B.tpi_window_slots(None, 16, 1))) == B.TPI_EINVAL
+    # file tier: the description and the files are checked before anything is created on a device
+    fblk = lambda path=b"/nonexistent/tpi_block", nbytes=16: B.tpi_window_file_block(path, 0, nbytes, 0, 0, None)
+    fmk = lambda *bs: (B.tpi_window_file_block * len(bs))(*bs)
+    cf = lib.tpi_window_create_files
+    assert cf(C.byref(h), 1, fmk(fblk()), 1, one_class, 0) == B.TPI_EINVAL               # no staging buffer
+    assert cf(C.byref(h), 1, fmk(fblk(path=None)), 1, one_class, 2) == B.TPI_EINVAL
+    assert cf(C.byref(h), 1, fmk(fblk()), 1, one_class, 2) == B.TPI_EINVAL
+    assert b"cannot open" in lib.tpi_last_error()
+    assert cf(C.byref(h), 0, fmk(fblk()), 1, one_class, 2) == B.TPI_EINVAL
+    assert cf(C.byref(h), 1, None, 1, one_class, 2) == B.TPI_EINVAL
+    assert lib.tpi_window_read_stats(None, None) == B.TPI_EINVAL
     assert lib.tpi_window_prefetch(None, 0) == B.TPI_EINVAL
     assert lib.tpi_window_destroy(None) == B.TPI_EINVAL
 

@@ -342,3 +342,125 @@ def test_block_window_with_retention_equals_resident_run_bitwise(L, w, T):
     for a, r in zip(got, ref):
         assert torch.equal(a, r)
 
+
+@pytest.mark.parametrize("L,w,T,one_file", [(5, 4, 0, True), (6, 2, 2, False), (4, 4, 3, True)])
+def test_file_tier_window_equals_resident_run_bitwise(tmp_path, L, w, T, one_file):
+    """The paper's source tier: blocks are byte ranges of files, a loader thread reads them into pinned
+    staging buffers and forwards them to the HBM slots.  Same block layout, slot classes and retention as the
+    block window; outputs equal the resident run bit for bit and the byte count is exact."""
+    h, nq, nkv, d, sl = 512, 4, 2, 64, 1024
+    pos0, n_tokens, max_seq = 9, 3, 16
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq)
+    shapes = synth.shard_tensor_shapes(h, nq, nkv, d, sl)
+    lay_a, n_a = _block_layout(shapes, ATTN_TENSORS)
+    lay_f, n_f = _block_layout(shapes, FFN_TENSORS)
+    rng = np.random.default_rng(1000 + 100 * L + 10 * w + T)
+    arrays = []
+    for l in range(L):
+        wts = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+        for lay, n in ((lay_a, n_a), (lay_f, n_f)):
+            blob = np.empty(n, np.float32)
+            for name, (off, cnt) in lay.items():
+                blob[off:off + cnt] = wts[name].reshape(-1)
+            arrays.append(blob)
+    files = []                                   # (path, offset, nbytes) per block
+    if one_file:
+        path = str(tmp_path / "stack.bin")
+        with open(path, "wb") as f:
+            for a in arrays:
+                files.append((path, f.tell(), a.nbytes))
+                f.write(a.tobytes())
+    else:
+        for b, a in enumerate(arrays):
+            path = str(tmp_path / f"block{b}.bin")
+            a.tofile(path)
+            files.append((path, 0, a.nbytes))
+    h0 = torch.from_numpy(rng.standard_normal(h).astype(np.float32)).cuda()
+
+    def fresh_kv():
+        g = torch.Generator(device="cuda"); g.manual_seed(5)
+        keep = []
+        for l in range(L):
+            K = torch.zeros((nkv, max_seq, d), device="cuda"); V = torch.zeros_like(K)
+            K[:, :pos0] = torch.randn((nkv, pos0, d), generator=g, device="cuda")
+            V[:, :pos0] = torch.randn((nkv, pos0, d), generator=g, device="cuda")
+            keep.append((K, V))
+        return keep, [B.make_kv(K, V) for K, V in keep]
+
+    def weights(attn_base, ffn_base):
+        wv = B.tpi_layer_weights()
+        for name, (off, _) in lay_a.items():
+            setattr(wv, name, attn_base + off * 4)
+        for name, (off, _) in lay_f.items():
+            setattr(wv, name, ffn_base + off * 4)
+        return wv
+
+    def run(get_block, release_block):
+        x = h0.clone()
+        part = torch.empty_like(x); h_attn = torch.empty_like(x); out = torch.empty_like(x)
+        ws = torch.empty(B.tpi_workspace_bytes(cfg, 1) // 4, device="cuda")
+        keep, kv = fresh_kv()
+        outs, src = [], x
+        for t in range(n_tokens):
+            for l in range(L):
+                B.tpi_shard_layer_decode(cfg, weights(get_block(2 * l), 0), kv[l], pos0 + t, B.TPI_PHASE_ATTN, src, part, ws)
+                B.tpi_star_reduce([part], src, h_attn)
+                release_block(2 * l)
+                B.tpi_shard_layer_decode(cfg, weights(0, get_block(2 * l + 1)), None, pos0 + t, B.TPI_PHASE_FFN, h_attn, part, ws)
+                B.tpi_star_reduce([part], h_attn, out)
+                release_block(2 * l + 1)
+                src = out.clone()
+            outs.append(src.clone())
+        torch.cuda.synchronize()
+        return outs
+
+    dev = [torch.from_numpy(a).cuda() for a in arrays]
+    ref = run(lambda b: dev[b].data_ptr(), lambda b: None)
+
+    retained = {2 * l + 1 for l in range(L) if T > 0 and l % T == 0}
+    homes = {b: torch.empty(n_f, device="cuda") for b in retained}
+    slots_a = torch.empty((w // 2) * n_a, device="cuda")
+    slots_f = torch.empty((w // 2) * n_f, device="cuda")
+    blocks = [(files[b][0], files[b][1], files[b][2], b % 2, homes.get(b)) for b in range(2 * L)]
+    win = B.Window.from_files(blocks, [(slots_a, n_a * 4, w // 2), (slots_f, n_f * 4, w // 2)], n_staging=2)
+    total = 2 * L * n_tokens
+    issued = [0]
+
+    def prefetch_next():
+        if issued[0] < total:
+            win.prefetch(issued[0] % (2 * L))
+            issued[0] += 1
+
+    for _ in range(w):
+        prefetch_next()
+
+    def release_block(b):
+        win.release(b)
+        prefetch_next()
+
+    got = run(lambda b: win.acquire(b), release_block)
+    _, copied = win.copy_stats()
+    per_token = L * n_a * 4 + sum(n_f * 4 for l in range(L) if (2 * l + 1) not in retained)
+    assert copied == n_tokens * per_token + len(retained) * n_f * 4
+    assert win.read_ms() > 0
+    win.destroy()
+    for a, r in zip(got, ref):
+        assert torch.equal(a, r)
+
+
+def test_file_tier_reports_a_short_file(tmp_path):
+    """A block that reaches past the end of its file: the loader thread stops and the failure is reported to
+    the caller at acquire, as an error code, not as a hang."""
+    n = 1024
+    path = str(tmp_path / "short.bin")
+    np.zeros(n // 2, np.float32).tofile(path)            # half of what the block claims
+    slots = torch.empty(2 * n, device="cuda")
+    win = B.Window.from_files([(path, 0, n * 4, 0, None)], [(slots, n * 4, 2)], n_staging=1)
+    win.prefetch(0)
+    with pytest.raises(B.TpiError) as ei:
+        win.acquire(0)
+    assert ei.value.code == B.TPI_ERUNTIME and "file ends inside the block" in str(ei.value)
+    with pytest.raises(B.TpiError):
+        win.prefetch(0)
+    win.destroy()
+
