@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--prefill-steps", type=int, default=3)
     ap.add_argument("--no-token-ends", action="store_true", help="skip embedding / task head / token choice")
     ap.add_argument("--vocab", type=int, default=32000)
+    ap.add_argument("--no-window-files", action="store_true", help="skip the file-tier window (weights read from files)")
+    ap.add_argument("--window-file-layers", type=int, default=16)
+    ap.add_argument("--window-file-readers", type=int, default=4)
     ap.add_argument("--no-window-blocks", action="store_true",
                     help="skip the block-granular window variants (attention / FFN blocks, FFN retention)")
     ap.add_argument("--window-retain-every", type=int, default=2,
@@ -227,12 +230,104 @@ def window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_
         "hidden_fraction": round(max(0.0, 1.0 - (ms - ms_resident) / copy_ms), 4),
         "compute_over_copy": round(ms_resident / copy_ms, 4), "output_finite": finite,
     }
+    if not args.no_window_files:
+        res["file_tier"] = window_files_variant(args, m, L, N, blobs, layout, cfg, KV_one, P_all, P_one, WS_one, h0, h_a,
+                                                h_b, h_attn, pos0, link_gbps)
     if not args.no_window_blocks and Wn >= 2:
         res["block_granular"] = [
             window_blocks_variant(args, m, L, N, blobs, host, layout, cfg, KV_one, P_all, P_one, WS_one, h0, h_a, h_b,
                                   h_attn, pos0, link_gbps, T)
             for T in (0, args.window_retain_every)]
     return res
+
+
+def window_files_variant(args, m, L, N, blobs, layout, cfg, KV_one, P_all, P_one, WS_one, h0, h_a, h_b, h_attn, pos0,
+                         link_gbps):
+    """The paper's source tier: the layer blobs of shard 0 are files, a loader thread reads them into two
+    pinned staging buffers and forwards them into the HBM slots.  --window-file-layers layers per token
+    (a token over all 80 would only repeat the same steady state); 8 distinct files, layer l uses file l % 8.
+    The files have just been written, so they are read through the page cache: the figure is the rate of
+    the loader path (pread into pinned memory, then the copy over the link), not of a disk."""
+    import shutil
+    import tempfile
+
+    import torch
+
+    from paper_2410_00531_amd import binding as B
+    from paper_2410_00531_amd import synth
+    dev = h0.device
+    Lf = min(args.window_file_layers, L)
+    Wn = min(args.window_layers, Lf)
+    D = min(8, Lf)
+    nfl = blobs[0][0].numel()
+    nbytes = nfl * 4
+    tmp = tempfile.mkdtemp(prefix="tpi_blobs_")
+    try:
+        paths = []
+        for i in range(D):
+            path = os.path.join(tmp, f"layer{i}.bin")
+            blobs[i][0].cpu().numpy().tofile(path)
+            paths.append(path)
+        slots = torch.empty(Wn * nfl, dtype=torch.float32, device=dev)
+        by_ptr = {}
+        for s_i in range(Wn):
+            w = (B.tpi_layer_weights * 1)()
+            base = slots.data_ptr() + s_i * nbytes
+            for name in synth.TENSOR_ORDER:
+                setattr(w[0], name, base + layout[name][0] * 4)
+            by_ptr[base] = w
+        win = B.Window.from_files([(paths[l % D], 0, nbytes, 0, None) for l in range(Lf)], [(slots, nbytes, Wn)],
+                                  n_staging=2, n_readers=args.window_file_readers)
+        lib = B.lib()
+        stream = torch.cuda.current_stream().cuda_stream
+        cfg_p = C.byref(cfg)
+        for l in range(Wn):
+            win.prefetch(l)
+        nxt = [Wn]
+
+        def check(rc):
+            if rc != 0:
+                raise RuntimeError(B.tpi_last_error())
+
+        def token(pos):
+            src, dst = h0, h_a
+            for l in range(Lf):
+                w = by_ptr[win.acquire(l)]
+                check(lib.tpi_shards_layer_decode(cfg_p, 1, w, KV_one[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
+                                                  P_one, WS_one, stream))
+                check(lib.tpi_star_reduce(P_all, N, m.hidden, src.data_ptr(), h_attn.data_ptr(), stream))
+                check(lib.tpi_shards_layer_decode(cfg_p, 1, w, None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
+                                                  P_one, WS_one, stream))
+                check(lib.tpi_star_reduce(P_all, N, m.hidden, h_attn.data_ptr(), dst.data_ptr(), stream))
+                win.release(l)
+                win.prefetch(nxt[0] % Lf)
+                nxt[0] += 1
+                src, dst = dst, (h_b if dst is h_a else h_a)
+            return src
+
+        token(pos0)
+        torch.cuda.synchronize()
+        r0 = win.read_ms()
+        t = time.perf_counter()
+        steps = max(1, min(2, args.window_steps))
+        for i in range(steps):
+            out = token(pos0 + 1 + i)
+        torch.cuda.current_stream().synchronize()
+        ms = (time.perf_counter() - t) * 1e3 / steps
+        read_ms = (win.read_ms() - r0) / steps
+        finite = bool(torch.isfinite(out).all().item())
+        win.destroy()
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
+    gb = Lf * nbytes / 1e9
+    return {
+        "layers_per_token": Lf, "window_layers": Wn, "staging_buffers": 2, "reader_threads": args.window_file_readers,
+        "files": D, "ms_per_token": round(ms, 2),
+        "gb_per_token": round(gb, 3), "loader_gbps": round(gb / (ms * 1e-3), 2),
+        "pread_ms_per_token": round(read_ms, 2), "pread_gbps": round(gb / (read_ms * 1e-3), 2) if read_ms > 0 else None,
+        "link_peak_gbps_plain_copy": round(link_gbps, 2), "source": "files read through the page cache",
+        "output_finite": finite,
+    }
 
 
 def window_blocks_variant(args, m, L, N, blobs, host, layout, cfg, KV_one, P_all, P_one, WS_one, h0, h_a, h_b, h_attn,

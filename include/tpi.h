@@ -262,7 +262,8 @@ int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_windo
  * The paper's own source tier: the weights stay in files ("dynamically loading
  * and unloading model weights", Sec. 3.3; the scheduler "operates on a daemon
  * thread").  Blocks are byte ranges of files; the window owns a loader thread
- * and n_staging pinned staging buffers of the largest block's size.  prefetch
+ * and n_staging pinned staging buffers of the largest block's size; a block of
+ * 1 MiB or more is read by n_readers threads (1..64), a contiguous part each.  prefetch
  * only queues the request and returns; the loader reads the block into the
  * next staging buffer (pread) and forwards it to its HBM slot on the window's
  * copy stream, strictly in request order.  acquire blocks the CALLING THREAD
@@ -285,7 +286,8 @@ typedef struct tpi_window_file_block {
 } tpi_window_file_block;
 
 int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window_file_block *blocks,
-                            int32_t n_classes, const tpi_window_slots *classes, int32_t n_staging);
+                            int32_t n_classes, const tpi_window_slots *classes, int32_t n_staging,
+                            int32_t n_readers);
 int tpi_window_read_stats(tpi_window *w, double *read_ms);
 /* Total time (ms) the copy stream spent in copies between the first prefetch
  * and the last one completed so far, and the bytes they moved; synchronises

@@ -120,7 +120,7 @@ def lib() -> C.CDLL:
                                                C.c_int32, C.POINTER(tpi_window_slots)]
         l.tpi_window_create_files.restype = C.c_int
         l.tpi_window_create_files.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.POINTER(tpi_window_file_block),
-                                              C.c_int32, C.POINTER(tpi_window_slots), C.c_int32]
+                                              C.c_int32, C.POINTER(tpi_window_slots), C.c_int32, C.c_int32]
         l.tpi_window_read_stats.restype = C.c_int
         l.tpi_window_read_stats.argtypes = [C.c_void_p, C.POINTER(C.c_double)]
         for name in ("tpi_window_prefetch",):
@@ -385,7 +385,7 @@ class Window:
         return self
 
     @classmethod
-    def from_files(cls, blocks, classes, n_staging: int = 2) -> "Window":
+    def from_files(cls, blocks, classes, n_staging: int = 2, n_readers: int = 1) -> "Window":
         """tpi_window_create_files.  blocks: sequence of (path, offset, nbytes, slot_class, resident);
         classes as in from_blocks."""
         self = cls.__new__(cls)
@@ -398,7 +398,8 @@ class Window:
         carr = (tpi_window_slots * len(classes))()
         for i, (base, slot_bytes, n_slots) in enumerate(classes):
             carr[i] = tpi_window_slots(_ptr(base), slot_bytes, n_slots)
-        _check(lib().tpi_window_create_files(C.byref(self._h), len(blocks), barr, len(classes), carr, n_staging))
+        _check(lib().tpi_window_create_files(C.byref(self._h), len(blocks), barr, len(classes), carr, n_staging,
+                                             n_readers))
         return self
 
     def read_ms(self) -> float:

@@ -11,6 +11,7 @@
 #include <fcntl.h>
 #include <unistd.h>
 
+#include <algorithm>
 #include <cerrno>
 #include <condition_variable>
 #include <cstring>
@@ -92,6 +93,7 @@ struct tpi_window {
     std::vector<hipEvent_t> staging_done;    // the staging buffer's last copy has left it
     std::vector<char> staging_used;
     size_t staging_bytes = 0;
+    int n_readers = 1;                       // threads that share the read of one block
     std::thread loader;
     std::mutex mu;
     std::condition_variable cv_req, cv_done;
@@ -200,21 +202,34 @@ void loader_main(tpi_window *w)
         hipError_t e = hipSuccess;
         if (w->staging_used[si]) e = hipEventSynchronize(w->staging_done[si]);   // its previous copy has left it
         if (e != hipSuccess) { loader_fail(w, std::string("hipEventSynchronize: ") + hipGetErrorString(e)); return; }
-        // read the block from its file
+        // read the block from its file: n_readers threads, a contiguous part each (this thread takes the first)
         timespec t0, t1;
         clock_gettime(CLOCK_MONOTONIC, &t0);
-        size_t got = 0;
         char *dst = static_cast<char *>(w->staging[si]);
-        while (got < b.bytes) {
-            ssize_t r = ::pread(b.fd, dst + got, b.bytes - got, (off_t)(b.file_offset + got));
-            if (r < 0 && errno == EINTR) continue;
-            if (r <= 0) {
-                loader_fail(w, r == 0 ? "block " + std::to_string(rq.block) + ": file ends inside the block"
-                                      : "block " + std::to_string(rq.block) + ": pread: " + std::strerror(errno));
-                return;
+        const int parts = (b.bytes >= ((size_t)1 << 20)) ? w->n_readers : 1;
+        const size_t per = ((b.bytes + parts - 1) / parts + 4095) & ~(size_t)4095;
+        std::vector<std::string> errs(parts);
+        auto read_part = [&](int p) {
+            size_t lo = std::min(b.bytes, (size_t)p * per), hi = std::min(b.bytes, lo + per);
+            while (lo < hi) {
+                ssize_t r = ::pread(b.fd, dst + lo, hi - lo, (off_t)(b.file_offset + lo));
+                if (r < 0 && errno == EINTR) continue;
+                if (r <= 0) {
+                    errs[p] = r == 0 ? "block " + std::to_string(rq.block) + ": file ends inside the block"
+                                     : "block " + std::to_string(rq.block) + ": pread: " + std::strerror(errno);
+                    return;
+                }
+                lo += (size_t)r;
             }
-            got += (size_t)r;
+        };
+        {
+            std::vector<std::thread> helpers;
+            for (int p = 1; p < parts; ++p) helpers.emplace_back(read_part, p);
+            read_part(0);
+            for (auto &t : helpers) t.join();
         }
+        for (const auto &msg : errs)
+            if (!msg.empty()) { loader_fail(w, msg); return; }
         clock_gettime(CLOCK_MONOTONIC, &t1);
         if (rq.after) e = hipStreamWaitEvent(w->copy, rq.after, 0);
         if (e == hipSuccess && !w->any_copy) e = hipEventRecord(w->first_begin, w->copy);
@@ -316,12 +331,13 @@ int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_windo
 }
 
 int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window_file_block *blocks, int32_t n_classes,
-                            const tpi_window_slots *classes, int32_t n_staging)
+                            const tpi_window_slots *classes, int32_t n_staging, int32_t n_readers)
 {
     if (!out) return fail(TPI_EINVAL, "out is null");
     *out = nullptr;
     if (n_blocks < 1 || !blocks) return fail(TPI_EINVAL, "null or empty block list");
     if (n_staging < 1) return fail(TPI_EINVAL, "n_staging %d < 1", n_staging);
+    if (n_readers < 1 || n_readers > 64) return fail(TPI_EINVAL, "n_readers %d outside [1, 64]", n_readers);
     std::vector<tpi_window_block> plain(n_blocks);
     size_t largest = 0;
     for (int i = 0; i < n_blocks; ++i) {
@@ -370,6 +386,7 @@ int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window
     };
     if (hipGetDevice(&w->device) != hipSuccess) return bail(fail(TPI_ERUNTIME, "hipGetDevice failed"));
     w->staging_bytes = largest;
+    w->n_readers = n_readers;
     w->staging.assign(n_staging, nullptr);
     w->staging_done.assign(n_staging, nullptr);
     w->staging_used.assign(n_staging, 0);

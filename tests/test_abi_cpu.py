@@ -134,12 +134,13 @@ def test_window_argument_errors_without_a_device():
     fblk = lambda path=b"/nonexistent/tpi_block", nbytes=16: B.tpi_window_file_block(path, 0, nbytes, 0, 0, None)
     fmk = lambda *bs: (B.tpi_window_file_block * len(bs))(*bs)
     cf = lib.tpi_window_create_files
-    assert cf(C.byref(h), 1, fmk(fblk()), 1, one_class, 0) == B.TPI_EINVAL               # no staging buffer
-    assert cf(C.byref(h), 1, fmk(fblk(path=None)), 1, one_class, 2) == B.TPI_EINVAL
-    assert cf(C.byref(h), 1, fmk(fblk()), 1, one_class, 2) == B.TPI_EINVAL
+    assert cf(C.byref(h), 1, fmk(fblk()), 1, one_class, 0, 1) == B.TPI_EINVAL            # no staging buffer
+    assert cf(C.byref(h), 1, fmk(fblk()), 1, one_class, 2, 0) == B.TPI_EINVAL            # no reader
+    assert cf(C.byref(h), 1, fmk(fblk(path=None)), 1, one_class, 2, 1) == B.TPI_EINVAL
+    assert cf(C.byref(h), 1, fmk(fblk()), 1, one_class, 2, 1) == B.TPI_EINVAL
     assert b"cannot open" in lib.tpi_last_error()
-    assert cf(C.byref(h), 0, fmk(fblk()), 1, one_class, 2) == B.TPI_EINVAL
-    assert cf(C.byref(h), 1, None, 1, one_class, 2) == B.TPI_EINVAL
+    assert cf(C.byref(h), 0, fmk(fblk()), 1, one_class, 2, 1) == B.TPI_EINVAL
+    assert cf(C.byref(h), 1, None, 1, one_class, 2, 1) == B.TPI_EINVAL
     assert lib.tpi_window_read_stats(None, None) == B.TPI_EINVAL
     assert lib.tpi_window_prefetch(None, 0) == B.TPI_EINVAL
     assert lib.tpi_window_destroy(None) == B.TPI_EINVAL

@@ -422,7 +422,8 @@ def test_file_tier_window_equals_resident_run_bitwise(tmp_path, L, w, T, one_fil
     slots_a = torch.empty((w // 2) * n_a, device="cuda")
     slots_f = torch.empty((w // 2) * n_f, device="cuda")
     blocks = [(files[b][0], files[b][1], files[b][2], b % 2, homes.get(b)) for b in range(2 * L)]
-    win = B.Window.from_files(blocks, [(slots_a, n_a * 4, w // 2), (slots_f, n_f * 4, w // 2)], n_staging=2)
+    win = B.Window.from_files(blocks, [(slots_a, n_a * 4, w // 2), (slots_f, n_f * 4, w // 2)], n_staging=2,
+                              n_readers=1 + L % 3)           # blocks of 1 MiB and more are read by several threads
     total = 2 * L * n_tokens
     issued = [0]
 
