@@ -211,7 +211,9 @@ def window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_
         return src
 
     token(pos0)                                  # warm-up token (the first window was preloaded)
-    torch.cuda.synchronize()
+    # only the compute stream: a device-wide wait would also let the copies of the next token's first layers
+    # finish before the clock starts, and the timed tokens would get them for free
+    torch.cuda.current_stream().synchronize()
     t = time.perf_counter()
     for i in range(args.window_steps):
         out = token(pos0 + 1 + i)
@@ -306,7 +308,7 @@ def window_files_variant(args, m, L, N, blobs, layout, cfg, KV_one, P_all, P_one
             return src
 
         token(pos0)
-        torch.cuda.synchronize()
+        torch.cuda.current_stream().synchronize()      # not the copy stream: see window_leg
         r0 = win.read_ms()
         t = time.perf_counter()
         steps = max(1, min(2, args.window_steps))
@@ -394,14 +396,14 @@ def window_blocks_variant(args, m, L, N, blobs, host, layout, cfg, KV_one, P_all
         return src
 
     token(pos0)                                  # warm-up token: brings the retained blocks in
-    torch.cuda.synchronize()
-    _, bytes0 = win.copy_stats()
+    torch.cuda.current_stream().synchronize()      # not the copy stream: see window_leg
+    bytes0 = win.bytes_copied()
     t = time.perf_counter()
     for i in range(args.window_steps):
         out = token(pos0 + 1 + i)
     torch.cuda.current_stream().synchronize()
     ms = (time.perf_counter() - t) * 1e3 / args.window_steps
-    _, bytes1 = win.copy_stats()
+    bytes1 = win.bytes_copied()
     finite = bool(torch.isfinite(out).all().item())
     win.destroy()
     per_token = (bytes1 - bytes0) / args.window_steps
@@ -502,11 +504,11 @@ def window_prefill_leg(args, m, seed):
         return s32
 
     def timed(fn, reps):
-        fn(); torch.cuda.synchronize()
+        fn(); torch.cuda.current_stream().synchronize()      # the compute stream only, at both ends
         t = time.perf_counter()
         for _ in range(reps):
             out = fn()
-        torch.cuda.synchronize()
+        torch.cuda.current_stream().synchronize()
         return (time.perf_counter() - t) * 1e3 / reps, out
 
     ms_res, out_res = timed(lambda: prompt(lambda l: res_w[l % D], lambda l: None), 2)

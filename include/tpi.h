@@ -290,8 +290,9 @@ int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window
                             int32_t n_readers);
 int tpi_window_read_stats(tpi_window *w, double *read_ms);
 /* Total time (ms) the copy stream spent in copies between the first prefetch
- * and the last one completed so far, and the bytes they moved; synchronises
- * the copy stream.  Either output may be NULL. */
+ * and the last one completed so far, and the bytes requested so far.  Either
+ * output may be NULL; asking for the time synchronises the copy stream, asking
+ * for the bytes alone waits for nothing. */
 int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes);
 
 /*

@@ -418,6 +418,12 @@ class Window:
     def release(self, layer: int, stream=None) -> None:
         _check(lib().tpi_window_release(self._h, layer, _stream(stream)))
 
+    def bytes_copied(self) -> int:
+        """Bytes requested so far; unlike copy_stats this does not wait for the copy stream."""
+        b = C.c_uint64()
+        _check(lib().tpi_window_copy_stats(self._h, None, C.byref(b)))
+        return b.value
+
     def copy_stats(self):
         ms, b = C.c_double(), C.c_uint64()
         _check(lib().tpi_window_copy_stats(self._h, C.byref(ms), C.byref(b)))

@@ -509,12 +509,14 @@ int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes)
 {
     if (!w) return fail(TPI_EINVAL, "window is null");
     if (w->file_tier) {
-        // everything requested so far must have been handed to the copy stream
         std::unique_lock<std::mutex> lk(w->mu);
-        w->cv_done.wait(lk, [&] { return w->n_issued >= w->n_requested || w->loader_failed; });
+        // the time span needs everything requested so far to have been handed to the copy stream
+        if (copy_ms) w->cv_done.wait(lk, [&] { return w->n_issued >= w->n_requested || w->loader_failed; });
         if (w->loader_failed) return fail(TPI_ERUNTIME, "loader thread: %s", w->loader_error.c_str());
+        if (bytes) *bytes = w->bytes_copied;
+    } else if (bytes) {
+        *bytes = w->bytes_copied;
     }
-    if (bytes) *bytes = w->bytes_copied;
     if (copy_ms) {
         *copy_ms = 0.0;
         if (w->any_copy) {
