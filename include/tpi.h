@@ -52,6 +52,7 @@ enum { TPI_PHASE_ATTN = 1, TPI_PHASE_FFN = 2 };
 #define TPI_MAX_HEAD_DIM 256
 #define TPI_ATTN_MAX_SPLITS 32    /* KV-length splits of the decode attention            */
 #define TPI_MAX_BATCH_SHARDS 16   /* shards one batched call can take                    */
+#define TPI_MAX_ROW 16384         /* decode: hidden, ffn_local and n_q_local * head_dim  */
 
 /* Shape of ONE device's shard of one decoder layer (Sec. 3.1 Step 1: attention
  * heads and FFN columns are divided among devices). */

@@ -102,13 +102,13 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
     if (pos < 0 || pos >= cfg->max_seq) return fail(TPI_EINVAL, "pos %d outside [0, max_seq %d)", pos, cfg->max_seq);
     if (cfg->dtype != TPI_F32) return fail(TPI_EUNSUPPORTED, "decode is built for fp32 only");
     if (!aligned16(h_in)) return fail(TPI_EUNSUPPORTED, "h_in is not 16-byte aligned");
-    // each stage keeps its input vector in LDS (64 KB per workgroup without opting in to more)
+    // each stage keeps its thread's slice of the input vector in registers: at most 16 chunks of 1024 floats
     {
         int64_t longest = cfg->hidden;
         if (cfg->ffn_local > longest) longest = cfg->ffn_local;
         if ((int64_t)cfg->n_q_local * cfg->head_dim > longest) longest = (int64_t)cfg->n_q_local * cfg->head_dim;
-        if (longest * 4 + 1024 > 65536)
-            return fail(TPI_EUNSUPPORTED, "vector of %lld floats does not fit the LDS staging buffer", (long long)longest);
+        if (longest > 16 * 1024)
+            return fail(TPI_EUNSUPPORTED, "rows of %lld floats: the GEMV stages are built for at most 16384", (long long)longest);
     }
 
     DecodeArgs a;

@@ -56,6 +56,12 @@ def test_workspace_bytes():
     assert B.tpi_workspace_bytes(cfg, 0) == 0
 
 
+def test_rows_longer_than_the_stages_are_built_for_are_refused():
+    kv = B.tpi_kv_layer(FAKE, FAKE)
+    for cfg in (B.make_cfg(16388, 2, 1, 64, 128, 8), B.make_cfg(256, 2, 1, 64, 16388, 8), B.make_cfg(256, 129, 1, 128, 64, 8)):
+        assert _code(B.tpi_shard_layer_decode, cfg, _w(), kv, 3, B.TPI_PHASE_ATTN, FAKE, FAKE, FAKE, stream=0) == B.TPI_EUNSUPPORTED
+
+
 def test_decode_argument_errors():
     good = B.make_cfg(256, 2, 2, 64, 344, 24)
     kv = B.tpi_kv_layer(FAKE, FAKE)

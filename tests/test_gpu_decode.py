@@ -106,6 +106,20 @@ def test_random_shapes_both_phases(h, nq, nkv, d, sl, pos, max_seq):
     check_ffn_phase(cfg, w, x)
 
 
+@pytest.mark.parametrize("h,nq,nkv,d,sl", [
+    (16384, 2, 1, 64, 128),      # the longest row the QKV and gate/up stages are built for (16 passes of 1024)
+    (256, 128, 1, 128, 16384),   # the same for the output projection (n_q * d = 16384) and the down projection
+])
+def test_longest_rows(h, nq, nkv, d, sl):
+    rng = np.random.default_rng(h + sl)
+    pos, max_seq = 5, 8
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq)
+    w, K, V = random_shard_np(rng, cfg, pos)
+    x = rng.standard_normal(h).astype(np.float32)
+    check_attn_phase(cfg, w, K, V, pos, x)
+    check_ffn_phase(cfg, w, x)
+
+
 @pytest.mark.parametrize("pos,max_seq", [
     (0, 1), (0, 8), (1, 8), (63, 64), (64, 65), (65, 130), (127, 128), (2047, 2048), (2048, 2100),
     (2111, 2112), (4500, 4501),
@@ -151,10 +165,11 @@ def test_large_positions_keep_rope_phase():
     check_attn_phase(cfg, w, K, V, pos, x, sentinel=False)
 
 
-def test_batched_call_equals_single_calls_bitwise():
+@pytest.mark.parametrize("n", [5, B.TPI_MAX_BATCH_SHARDS])
+def test_batched_call_equals_single_calls_bitwise(n):
     rng = np.random.default_rng(6)
     cfg = B.make_cfg(512, 4, 2, 64, 256, 80)
-    pos, n = 70, 5
+    pos = 70
     data = [random_shard_np(rng, cfg, pos) for _ in range(n)]
     x = torch.from_numpy(rng.standard_normal(512).astype(np.float32)).cuda()
     a = [GpuShard(cfg, *d) for d in data]
