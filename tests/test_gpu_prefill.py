@@ -74,6 +74,7 @@ def _run_prefill_case(h, nq, nkv, d, sl, n, pos0, max_seq, seed, attn_scale=1.0)
     (192, 2, 1, 96, 64, 45, 2),        # head_dim 96: three 32-wide output tiles
     (96, 4, 2, 48, 40, 33, 0),         # head_dim not a multiple of 32: the vector-ALU attention
     (512, 16, 1, 64, 128, 150, 1),     # 16 query heads per KV head: a row tile covers two tokens
+    (128, 4, 2, 32, 64, 1500, 37),     # long prompt on top of a cache: 48 key tiles, 12 rounds per wave
 ])
 def test_prefill_parity_small_shapes(h, nq, nkv, d, sl, n, pos0):
     _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + 3, seed=h + n + pos0, attn_scale=4.0)
