@@ -57,11 +57,26 @@ __device__ __forceinline__ float wsum(float v)
 __global__ __launch_bounds__(256) void k_rmsnorm_bf16(const bf16_t *__restrict__ x, const float *__restrict__ g,
                                                       bf16_t *__restrict__ out, int h, float eps)
 {
+    // the first kKeep * 2048 elements of the row stay in registers between the two passes (rows up to
+    // 8192 elements are read once); longer rows read the rest again
+    constexpr int kKeep = 4;
     __shared__ float red[4];
     const bf16_t *xr = x + (size_t)blockIdx.x * h;
     bf16_t *orow = out + (size_t)blockIdx.x * h;
+    uint4 keep[kKeep];
+#pragma unroll
+    for (int c = 0; c < kKeep; ++c) {
+        const int k = (c * 256 + threadIdx.x) * 8;
+        keep[c] = (k < h) ? *reinterpret_cast<const uint4 *>(xr + k) : make_uint4(0, 0, 0, 0);
+    }
     float ss = 0.f;
-    for (int k = threadIdx.x * 8; k < h; k += 256 * 8) {
+#pragma unroll
+    for (int c = 0; c < kKeep; ++c) {
+        const bf16_t *e = reinterpret_cast<const bf16_t *>(&keep[c]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { float v = bf16_to_f32(e[i]); ss = fmaf(v, v, ss); }
+    }
+    for (int k = (kKeep * 256 + threadIdx.x) * 8; k < h; k += 256 * 8) {
         uint4 raw = *reinterpret_cast<const uint4 *>(xr + k);
         const bf16_t *e = reinterpret_cast<const bf16_t *>(&raw);
 #pragma unroll
@@ -71,8 +86,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bf16(const bf16_t *__restrict__
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
     const float rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)h + eps);
-    for (int k = threadIdx.x * 8; k < h; k += 256 * 8) {
-        uint4 raw = *reinterpret_cast<const uint4 *>(xr + k);
+    auto emit = [&](int k, const uint4 &raw) {
         const bf16_t *e = reinterpret_cast<const bf16_t *>(&raw);
         float4 g0 = *reinterpret_cast<const float4 *>(g + k), g1 = *reinterpret_cast<const float4 *>(g + k + 4);
         const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
@@ -81,7 +95,13 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bf16(const bf16_t *__restrict__
 #pragma unroll
         for (int i = 0; i < 8; ++i) oe[i] = f32_to_bf16(bf16_to_f32(e[i]) * rinv * gg[i]);
         *reinterpret_cast<uint4 *>(orow + k) = o;
+    };
+#pragma unroll
+    for (int c = 0; c < kKeep; ++c) {
+        const int k = (c * 256 + threadIdx.x) * 8;
+        if (k < h) emit(k, keep[c]);
     }
+    for (int k = (kKeep * 256 + threadIdx.x) * 8; k < h; k += 256 * 8) emit(k, *reinterpret_cast<const uint4 *>(xr + k));
 }
 
 // ---------------------------------------------------------------------------
@@ -106,23 +126,32 @@ struct GemmArgs {
     int lda, ldb, ldc;
     int k_per_split;          // multiple of 64
     size_t c_split;           // floats between the partial products of consecutive splits
+    bf16_t *act;              // SWI kernels only: [M][n_split] output of the fused SwiGLU
 };
 
 // KW = 2: eight waves; waves 4..7 repeat the 2 x 2 arrangement and take the second half of every
 // K-step (a second wave per SIMD, so one wave's LDS and barrier waits are covered by the other's
-// MFMAs); their accumulators are added to those of waves 0..3 through LDS at the end.
+// MFMAs); at the end the two waves of a pair exchange halves of their accumulators through LDS and
+// each finishes one of the pair's two row tiles.
+//
+// SWI: the gate | up product with SwiGLU (Eq. 4's activation) applied to the accumulators.  Column
+// tile x then covers hidden units 64x .. 64x+63 of BOTH matrices, arranged so that each wave's first
+// 32x32 tile holds gate columns and its second the up columns of the same 32 units: the product
+// silu(gate) * up is taken lane by lane in registers and only the bf16 activation [M][n_split] is
+// written (no fp32 product in memory, no separate elementwise pass).
 constexpr int kSwzShift = 1;
 
-template <int BM, int BN, int NS, int KW>
+template <int BM, int BN, int NS, int KW, bool SWI = false>
 __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
 {
+    static_assert(!SWI || BN == 128, "the fused activation pairs the two 32-column tiles of a wave");
     constexpr int BK = 64, NT = 256 * KW;
     constexpr int MI = BM / 64, NI = BN / 64;           // 32x32 tiles per wave along m and n
     constexpr int ACH = BM * (BK / 8) / NT;             // 16-byte chunks per thread, A tile
     constexpr int BCH = BN * (BK / 8) / NT;
     constexpr int STAGE = (BM + BN) * 8;                // chunks per stage
     static_assert(ACH >= 1 && BCH >= 1, "tile too small for the thread count");
-    static_assert(KW == 1 || 4 * MI * NI * 16 * 64 * 4 <= 2 * STAGE * 16, "accumulator exchange must fit the LDS stages");
+    static_assert(KW == 1 || 8 * NI * 16 * 64 * 4 <= 2 * STAGE * 16, "accumulator exchange must fit the LDS stages");
     __shared__ uint4 lds[2 * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
@@ -144,8 +173,14 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     }
 #pragma unroll
     for (int i = 0; i < BCH; ++i) {
-        int n = min(n0 + ((tid + i * NT) >> 3), g.N - 1);
-        pb[i] = (n < g.n_split) ? g.B0 + (size_t)n * g.ldb : g.B1 + (size_t)(n - g.n_split) * g.ldb;
+        if constexpr (SWI) {
+            const int within = (tid + i * NT) >> 3;      // tile column: wave half, gate/up tile, unit
+            const int unit = min((int)blockIdx.x * 64 + (within >> 6) * 32 + (within & 31), g.n_split - 1);
+            pb[i] = ((within & 32) ? g.B1 : g.B0) + (size_t)unit * g.ldb;
+        } else {
+            int n = min(n0 + ((tid + i * NT) >> 3), g.N - 1);
+            pb[i] = (n < g.n_split) ? g.B0 + (size_t)n * g.ldb : g.B1 + (size_t)(n - g.n_split) * g.ldb;
+        }
     }
     // (row * 8 + chunk) -> swizzled LDS position; row & 7 == (tid >> 3) & 7 for every i
     const int st_off = (tid >> 3) * 8 + ((tid & 7) ^ ((tid >> (3 + kSwzShift)) & 7));
@@ -248,39 +283,58 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     };
     for (int k0 = k_begin; k0 < k_end; k0 += NS * BK) round(round, std::integral_constant<int, 0>{}, k0);
 
-    if constexpr (KW == 2) {
-        // the loop ended with a barrier: the stages are free
+    // KW = 2: the two waves of a pair hold partial sums of the same tiles.  Wave kh hands the other its
+    // partial of row tile 1 - kh through LDS and finishes row tile kh, so all eight waves share the stores.
+    auto give = [&](auto A) {
+        constexpr int a = decltype(A)::value;
         float *xf = reinterpret_cast<float *>(lds);
-        if (kh == 1) {
 #pragma unroll
-            for (int a = 0; a < MI; ++a)
+        for (int b = 0; b < NI; ++b)
 #pragma unroll
-                for (int b = 0; b < NI; ++b)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) xf[(((wave * MI + a) * NI + b) * 16 + r) * 64 + lane] = acc[a][b][r];
-        }
-        __syncthreads();
-        if (kh == 1) return;
-#pragma unroll
-        for (int a = 0; a < MI; ++a)
+            for (int r = 0; r < 16; ++r) xf[(((wave * 2 + a) * NI + b) * 16 + r) * 64 + lane] = acc[a][b][r];
+    };
+    // accumulator register r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of its 32x32 tile
+    auto finish = [&](auto A, bool take) {
+        constexpr int a = decltype(A)::value;
+        if (take) {
+            const float *xf = reinterpret_cast<const float *>(lds);
 #pragma unroll
             for (int b = 0; b < NI; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[a][b][r] += xf[(((wave * MI + a) * NI + b) * 16 + r) * 64 + lane];
-    }
-
-    // accumulator register r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of its 32x32 tile
-#pragma unroll
-    for (int a = 0; a < MI; ++a)
-#pragma unroll
-        for (int b = 0; b < NI; ++b) {
-            int col = n0 + wn * (BN / 2) + b * 32 + (lane & 31);
+                for (int r = 0; r < 16; ++r) acc[a][b][r] += xf[(((wave * 2 + a) * NI + b) * 16 + r) * 64 + lane];
+        }
+        if constexpr (SWI) {
+            const int unit = (int)blockIdx.x * 64 + wn * 32 + (lane & 31);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row < g.M && col < g.N) C[(size_t)row * g.ldc + col] = acc[a][b][r];
+                const float gt = acc[a][0][r], up = acc[a][NI - 1][r];
+                if (row < g.M && unit < g.n_split) g.act[(size_t)row * g.n_split + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < NI; ++b) {
+                int col = n0 + wn * (BN / 2) + b * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (row < g.M && col < g.N) C[(size_t)row * g.ldc + col] = acc[a][b][r];
+                }
             }
         }
+    };
+    if constexpr (KW == 2) {
+        static_assert(MI == 2, "one row tile per wave of a pair");
+        // the loop ended with a barrier: the stages are free
+        if (kh == 0) give(std::integral_constant<int, 1>{});
+        else give(std::integral_constant<int, 0>{});
+        __syncthreads();
+        if (kh == 0) finish(std::integral_constant<int, 0>{}, true);
+        else finish(std::integral_constant<int, 1>{}, true);
+    } else {
+        finish(std::integral_constant<int, 0>{}, false);
+        if constexpr (MI == 2) finish(std::integral_constant<int, 1>{}, false);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -722,13 +776,28 @@ hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t 
 {
     const GemmPlan p = plan_gemm(M, N, K, max_splits);
     if (n_parts) *n_parts = p.splits;
-    GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc, p.k_per_split, (size_t)M * ldc};
+    GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc, p.k_per_split, (size_t)M * ldc, nullptr};
     ProfScope ps(kStagePrefillGemm, st);
     dim3 grid(cdiv(N, p.bn), cdiv(M, p.bm), p.splits);
     if (p.bm == 128) hipLaunchKernelGGL((k_gemm_bf16_nt<128, 128, 4, 2>), grid, dim3(512), 0, st, g);
     else if (p.bn == 128) hipLaunchKernelGGL((k_gemm_bf16_nt<64, 128, 4, 1>), grid, dim3(256), 0, st, g);
     else hipLaunchKernelGGL((k_gemm_bf16_nt<64, 64, 4, 1>), grid, dim3(256), 0, st, g);
     return hipGetLastError();
+}
+
+// act[m][j] = bf16(silu(A . gate[j]) * (A . up[j])) in one launch.  False (nothing launched) when the
+// plan for this shape uses 64-column tiles: the caller then multiplies and activates separately.
+bool launch_gemm_swiglu(const bf16_t *A, int lda, const bf16_t *gate, const bf16_t *up, int sl, int ldb, bf16_t *act, int M,
+                        int K, hipStream_t st)
+{
+    const GemmPlan p = plan_gemm(M, 2 * sl, K, 1);
+    if (p.bn != 128) return false;
+    GemmArgs g{A, gate, up, nullptr, M, 2 * sl, K, sl, lda, ldb, 0, p.k_per_split, 0, act};
+    ProfScope ps(kStagePrefillGemm, st);
+    dim3 grid(cdiv(sl, 64), cdiv(M, p.bm), 1);
+    if (p.bm == 128) hipLaunchKernelGGL((k_gemm_bf16_nt<128, 128, 4, 2, true>), grid, dim3(512), 0, st, g);
+    else hipLaunchKernelGGL((k_gemm_bf16_nt<64, 128, 4, 1, true>), grid, dim3(256), 0, st, g);
+    return true;
 }
 
 }  // namespace
@@ -818,10 +887,12 @@ int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi
         hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n), dim3(256), 0, st, (const bf16_t *)h_in, (const float *)w->ffn_norm,
                            xn, h, c->rms_eps);
         TPI_LAUNCH_OK();
-        e = launch_gemm(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, big, 2 * sl, n, 2 * sl, h, st);
-        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
-        const size_t tot = (size_t)n * sl;
-        hipLaunchKernelGGL(k_swiglu, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, big, act, n, sl);
+        if (!launch_gemm_swiglu(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, act, n, h, st)) {
+            e = launch_gemm(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, big, 2 * sl, n, 2 * sl, h, st);
+            if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+            const size_t tot = (size_t)n * sl;
+            hipLaunchKernelGGL(k_swiglu, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, big, act, n, sl);
+        }
         TPI_LAUNCH_OK();
         e = launch_gemm(act, sl, (const bf16_t *)w->w_down, (const bf16_t *)w->w_down, h, sl, partial_out, h, n, h, sl, st);
         if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));

@@ -75,6 +75,9 @@ def _run_prefill_case(h, nq, nkv, d, sl, n, pos0, max_seq, seed, attn_scale=1.0)
     (96, 4, 2, 48, 40, 33, 0),         # head_dim not a multiple of 32: the vector-ALU attention
     (512, 16, 1, 64, 128, 150, 1),     # 16 query heads per KV head: a row tile covers two tokens
     (128, 4, 2, 32, 64, 1500, 37),     # long prompt on top of a cache: 48 key tiles, 12 rounds per wave
+    (264, 2, 1, 64, 2776, 300, 0),     # gate|up with the activation in its epilogue (128-row tiles), ragged rows, units and K
+    (128, 2, 1, 64, 8200, 40, 5),      # the same with 64-row tiles
+    (8456, 2, 1, 64, 64, 9, 0),        # token rows longer than what the RMSNorm keeps in registers
 ])
 def test_prefill_parity_small_shapes(h, nq, nkv, d, sl, n, pos0):
     _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + 3, seed=h + n + pos0, attn_scale=4.0)
