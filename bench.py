@@ -632,11 +632,11 @@ def prefill_leg(args, m, L, N, seed):
 
 
 # HBM bytes of one k_gate_up launch as the byte counters saw them (rocprofv3 --pmc FETCH_SIZE, then
-# WRITE_SIZE, KiB per dispatch, each scaled by 2.0: the factor by which the same counters under-read a plain
-# 1 GiB device copy).  A figure from separate profiler runs of this command, kept in profiles/; None for a
-# workload those runs did not cover.
+# WRITE_SIZE, KiB per dispatch, each scaled by what the same counter reads for a plain 1 GiB device copy: FETCH_SIZE
+# reads half of the copy's bytes (factor 2.0), WRITE_SIZE all of them (factor 1.0)).  A figure from separate profiler
+# runs of this command, kept in profiles/; None for a workload those runs did not cover.
 MEASURED_GATE_UP_TRAFFIC = {
-    ("llama2-70b-shaped-tp8", 8): {"bytes": round((918724.6 + 451.1) * 2.0 * 1024),
+    ("llama2-70b-shaped-tp8", 8): {"bytes": round((918720.8 * 2.0 + 450.6 * 1.0) * 1024),
                                    "source": "profiles/decode_70b_tp8_eight_shards_per_launch.md"},
 }
 
