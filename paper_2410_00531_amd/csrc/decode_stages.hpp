@@ -33,9 +33,18 @@ __device__ __forceinline__ float norm_slice(const float *x, const float *g, int 
 template <int ROWS>
 __device__ __forceinline__ float pick_own(const float (&y)[ROWS], int i)
 {
+    // Each candidate is pinned in a register first.  Left to itself the compiler selects among the
+    // ADDRESSES of y[r] instead, which turns y into an indexed array in LDS -- and the code that finds a
+    // thread's slot of such an array reads the workgroup size from the dispatch packet, which sits in
+    // host memory: microseconds per workgroup.
     float v = y[0];
+    asm volatile("" : "+v"(v));
 #pragma unroll
-    for (int r = 1; r < ROWS; ++r) v = (i == r) ? y[r] : v;
+    for (int r = 1; r < ROWS; ++r) {
+        float yr = y[r];
+        asm volatile("" : "+v"(yr));
+        v = (i == r) ? yr : v;
+    }
     return v;
 }
 
