@@ -137,6 +137,11 @@ template <int PAIRS, int KCH, int UB>
 __device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
                                           float *rope)
 {
+    // Every scalar argument the stage needs is requested here, in one batch: read where they are first used,
+    // the loads from the argument block form a chain of round trips (shape, then branch, then pointer) ahead
+    // of the first weight request.  The other stages begin the same way.
+    asm volatile("" ::"s"(a.h), "s"(a.nq), "s"(a.nkv), "s"(a.d), "s"(a.max_seq), "s"(a.pos), "s"(a.eps), "s"(a.h_in),
+                 "s"(s.w_qkv), "s"(s.attn_norm), "s"(s.ws), "s"(s.k), "s"(s.v), "s"(a.ws_q), "s"(a.ws_cnt));
     constexpr int ROWS = 2 * PAIRS;
     const int half = a.d / 2;
     const int npairs = (a.nq + 2 * a.nkv) * half;
@@ -186,6 +191,7 @@ template <int ROWS, int KCH, int UB, bool FOLD, int NP = kMaxBatchShards>
 __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
                                             const FusedReduce &rf)
 {
+    asm volatile("" ::"s"(a.h), "s"(a.nq), "s"(a.d), "s"(s.w_o), "s"(s.ws), "s"(a.ws_o), "s"(s.partial_out));
     const int dq = a.nq * a.d;
     const int n_units = (a.h + ROWS - 1) / ROWS;
     auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
@@ -239,6 +245,8 @@ __device__ __forceinline__ void stage_oproj(const DecodeDims &a, const ShardView
 template <int COLS, int KCH, int UB>
 __device__ __forceinline__ void stage_gate_up(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red)
 {
+    asm volatile("" ::"s"(a.h), "s"(a.sl), "s"(a.eps), "s"(a.h_in), "s"(s.w_gate), "s"(s.w_up), "s"(s.ffn_norm), "s"(s.ws),
+                 "s"(a.ws_act));
     constexpr int ROWS = 2 * COLS;
     const int n_units = (a.sl + COLS - 1) / COLS;
     auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
@@ -275,6 +283,7 @@ template <int ROWS, int KCH, int UB, bool FOLD, int NP = kMaxBatchShards>
 __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,
                                            const FusedReduce &rf)
 {
+    asm volatile("" ::"s"(a.h), "s"(a.sl), "s"(s.w_down), "s"(s.ws), "s"(a.ws_act), "s"(s.partial_out));
     const int n_units = (a.h + ROWS - 1) / ROWS;
     auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
 #pragma unroll
