@@ -889,7 +889,11 @@ def main():
                       "hbm_frac_of_peak": round(gbps_one / HBM_PEAK_GBPS, 4),
                       "gate_up_kernel_avg_us": round(gu1_avg_ms * 1e3, 2),
                       "gate_up_kernel_gbps": round(gu1_bytes / (gu1_avg_ms * 1e-3) / 1e9, 1) if gu1_n else None,
-                      "ms_per_token_reduce_folded_into_phase": round(fused_ms, 4) if fused_ms else None},
+                      # the same pass through the entry point that sums the peers' partials in the epilogue of the
+                      # row-parallel kernels (5 launches per layer instead of 7): what a device of the star would call
+                      "ms_per_token_reduce_folded_into_phase": round(fused_ms, 4) if fused_ms else None,
+                      "hbm_gbps_reduce_folded": round(bytes_one / (fused_ms * 1e-3) / 1e9, 1) if fused_ms else None,
+                      "hbm_frac_of_peak_reduce_folded": round(bytes_one / (fused_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4) if fused_ms else None},
         "roofline": {"kernel": f"k_gate_up (RMSNorm + gate/up GEMV + SiLU gate, {n_launch_shards} shard(s) per launch)",
                      "bound": "hbm", "achieved": round(gu_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gu_gbps / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(m, n_launch_shards),
