@@ -209,6 +209,48 @@ def test_reduce_folded_into_the_phase_is_bitwise_the_two_call_sequence():
             assert torch.equal(xin, want)
 
 
+def test_token_captured_in_a_graph_replays_to_the_eager_result():
+    """The decode entry points only enqueue kernels on the caller's stream, so a whole token (phases and
+    reduces of several layers, batched and folded variants) can be captured once and replayed.  Every replay,
+    with eager work and synchronisations in between, must reproduce the eager token bit for bit."""
+    rng = np.random.default_rng(77)
+    n_layers, n_sh, h, pos = 3, 2, 512, 21
+    cfg = B.make_cfg(h, 4, 2, 64, 264, 40)
+    layers = [[GpuShard(cfg, *random_shard_np(rng, cfg, pos)) for _ in range(n_sh)] for _ in range(n_layers)]
+    x0 = torch.from_numpy(rng.standard_normal(h).astype(np.float32)).cuda()
+    hs = [torch.empty(h, device="cuda") for _ in range(3)]
+
+    def token(folded):
+        src, mid, dst = x0, hs[0], hs[1]
+        for sh in layers:
+            for phase, a, b in ((B.TPI_PHASE_ATTN, src, mid), (B.TPI_PHASE_FFN, mid, dst)):
+                if folded:   # shard 1's partial first, then shard 0 with the reduce in its epilogue
+                    B.tpi_shard_layer_decode(cfg, sh[1].weights, sh[1].kv, pos, phase, a, sh[1].partial, sh[1].ws)
+                    B.tpi_shard_layer_decode_reduce(cfg, sh[0].weights, sh[0].kv, pos, phase, a, 0,
+                                                    [sh[0].partial, sh[1].partial], b, sh[0].ws)
+                else:
+                    B.tpi_shards_layer_decode(cfg, [s.weights for s in sh], [s.kv for s in sh], pos, phase, a,
+                                              [s.partial for s in sh], [s.ws for s in sh])
+                    B.tpi_star_reduce([s.partial for s in sh], a, b)
+            src, dst = dst, (hs[2] if dst is hs[1] else hs[1])
+        return src
+
+    for folded in (False, True):
+        want = token(folded).clone()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            out = token(folded)
+        for rep in range(3):
+            for t in hs: t.fill_(float("nan"))           # eager work between the replays
+            for sh in layers:
+                for s in sh: s.partial.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, want), f"replay {rep}, folded={folded}"
+
+
 def test_8b_shaped_layer_all_shards():
     """BASELINE config 2 shape: one layer, N = 4, KV length 512."""
     m = configs.LLAMA31_8B_TP4
