@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true", help="skip the bf16 prefill leg")
     ap.add_argument("--prefill-tokens", type=int, default=512)
     ap.add_argument("--prefill-steps", type=int, default=3)
+    ap.add_argument("--prefill-streams", type=int, default=2,
+                    help="also time the prompt with the emulated shards dealt to this many streams (<= 1: skip)")
     ap.add_argument("--no-token-ends", action="store_true", help="skip embedding / task head / token choice")
     ap.add_argument("--vocab", type=int, default=32000)
     ap.add_argument("--no-window-files", action="store_true", help="skip the file-tier window (weights read from files)")
@@ -609,6 +611,48 @@ def prefill_leg(args, m, L, N, seed):
         out = step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t) * 1e3 / K
+
+    # The N emulated shards are independent between the reduces: dealt to S streams (default priority), a
+    # shard's small kernels (norm, rotary scatter, attention) run beside another shard's GEMMs.
+    def step_streams(streams, wss, ev_in, ev_out):
+        main = torch.cuda.current_stream()
+        S = len(streams)
+        s32, s16 = x32, x16
+
+        def phase(l, ph, src16):
+            ev_in.record(main)
+            for st in streams:
+                st.wait_event(ev_in)
+            for r in range(N):
+                check(lib.tpi_shard_layer_prefill(cfg_p, C.byref(Wl[l][r]), C.byref(KVl[l][r]) if ph == B.TPI_PHASE_ATTN else None,
+                                                  0, n, ph, src16.data_ptr(), parts[r].data_ptr(),
+                                                  wss[r % S].data_ptr(), streams[r % S].cuda_stream))
+            for i, st in enumerate(streams):
+                ev_out[i].record(st)
+                main.wait_event(ev_out[i])
+
+        for l in range(L):
+            phase(l, B.TPI_PHASE_ATTN, s16)
+            check(lib.tpi_star_reduce_bf16(P, N, n * h, s32.data_ptr(), ha32.data_ptr(), ha16.data_ptr(), stream))
+            phase(l, B.TPI_PHASE_FFN, ha16)
+            check(lib.tpi_star_reduce_bf16(P, N, n * h, ha32.data_ptr(), hb32.data_ptr(), hb16.data_ptr(), stream))
+            s32, s16 = hb32, hb16
+        return s32
+
+    by_streams = {}
+    for S in ([] if args.prefill_streams <= 1 else [args.prefill_streams]):
+        streams = [torch.cuda.Stream() for _ in range(S)]
+        wss = [torch.empty_like(ws) for _ in range(S)]
+        ev_in = torch.cuda.Event(); ev_out = [torch.cuda.Event() for _ in range(S)]
+        ref = out.clone()
+        got = step_streams(streams, wss, ev_in, ev_out); torch.cuda.synchronize()
+        same = bool(torch.equal(got, ref))
+        t = time.perf_counter()
+        for _ in range(K):
+            step_streams(streams, wss, ev_in, ev_out)
+        torch.cuda.synchronize()
+        by_streams[S] = {"ms_per_prompt": round((time.perf_counter() - t) * 1e3 / K, 3), "output_equal_to_one_stream": same}
+        del streams, wss
     B.tpi_prof_enable(B.TPI_STAGE_PREFILL_GEMM, 4 * N * L)
     step(); torch.cuda.synchronize()
     gemm_ms, gemm_n = B.tpi_prof_read()
@@ -617,9 +661,14 @@ def prefill_leg(args, m, L, N, seed):
     attn_flops = 2.0 * nq * d * n * (n + 1)
     total = (gemm_flops + attn_flops) * N * L
     peak = 2500.0
+    ms_one_stream, n_streams = ms, 1
+    for S, v in by_streams.items():          # the prompt's time is the better arrangement of the same launches
+        if v["output_equal_to_one_stream"] and v["ms_per_prompt"] < ms:
+            ms, n_streams = v["ms_per_prompt"], S
     return {
         "workload": f"{m.name}-prefill-{n}-tokens", "dtype": "bf16 (fp32 accumulate, fp32 partials)",
         "layers": L, "shards_emulated": N, "steps": K, "ms_per_prompt": round(ms, 3),
+        "streams": n_streams, "ms_per_prompt_one_stream": round(ms_one_stream, 3),
         "prompt_tokens_per_s": round(n / (ms * 1e-3), 1), "tflop_per_prompt": round(total / 1e12, 2),
         "tflops": round(total / (ms * 1e-3) / 1e12, 1), "mfma_frac_of_peak_whole_step": round(total / (ms * 1e-3) / 1e12 / peak, 4),
         "gemm_kernels": {"launches": gemm_n, "total_ms": round(gemm_ms, 3),
@@ -627,6 +676,7 @@ def prefill_leg(args, m, L, N, seed):
                          "frac_of_bf16_peak": round(gemm_flops * N * L / (gemm_ms * 1e-3) / 1e12 / peak, 4) if gemm_n else None,
                          "peak_tflops": peak},
         "reduce_gb_per_prompt": round(2 * L * (N + 2) * n * h * 4 / 1e9 + 2 * L * n * h * 2 / 1e9, 2),
+        "shards_on_streams": {str(k): v for k, v in by_streams.items()} or None,
         "output_finite": bool(torch.isfinite(out).all().item()),
     }
 
