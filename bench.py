@@ -644,7 +644,8 @@ def prefill_leg(args, m, L, N, seed):
         streams = [torch.cuda.Stream() for _ in range(S)]
         wss = [torch.empty_like(ws) for _ in range(S)]
         ev_in = torch.cuda.Event(); ev_out = [torch.cuda.Event() for _ in range(S)]
-        ref = out.clone()
+        B.tpi_set_prefill_concurrency(S)            # the GEMM plans size their grids for 1/S of the chip
+        ref = step().clone()                        # same plans on one stream: the results must be the same bits
         got = step_streams(streams, wss, ev_in, ev_out); torch.cuda.synchronize()
         same = bool(torch.equal(got, ref))
         t = time.perf_counter()
@@ -652,6 +653,7 @@ def prefill_leg(args, m, L, N, seed):
             step_streams(streams, wss, ev_in, ev_out)
         torch.cuda.synchronize()
         by_streams[S] = {"ms_per_prompt": round((time.perf_counter() - t) * 1e3 / K, 3), "output_equal_to_one_stream": same}
+        B.tpi_set_prefill_concurrency(1)
         del streams, wss
     B.tpi_prof_enable(B.TPI_STAGE_PREFILL_GEMM, 4 * N * L)
     step(); torch.cuda.synchronize()

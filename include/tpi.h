@@ -165,6 +165,19 @@ int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *h
                             void *stream);
 
 /*
+ * Hint for the prefill's GEMM plans, for callers that run several prefill
+ * calls side by side on different streams (the emulated shards of one layer
+ * are independent between the all-reduces of Eq. 1 and Eq. 2): each call then
+ * sizes its grids for 1/n_calls of the chip, which lets it take wider tiles.
+ * Process-wide, takes effect for later calls, default 1.  The sum of one
+ * output element runs over the contraction index in an order that depends on
+ * the plan, so results under different hints agree within the bf16 tolerance,
+ * not bit for bit; under one hint they are reproducible.
+ * Errors: TPI_EINVAL outside [1, TPI_MAX_BATCH_SHARDS].
+ */
+int tpi_set_prefill_concurrency(int32_t n_calls);
+
+/*
  * Star all-reduce sum as the master performs it (Sec. 3.2, Prop. 2; the
  * "+ H" shortcut of Eq. 1 and Eq. 2):
  *   out[i] = (((p0[i] + p1[i]) + p2[i]) + ... + p_{n-1}[i]) + residual[i]

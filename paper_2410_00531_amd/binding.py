@@ -23,7 +23,7 @@ TPI_MAX_REDUCE_RANKS = 64
 TPI_MAX_BATCH_SHARDS = 16
 
 EXPORTED = (
-    "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode",
+    "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode", "tpi_set_prefill_concurrency",
     "tpi_shard_layer_decode_reduce",
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create",
     "tpi_window_create_blocks", "tpi_window_create_files", "tpi_window_read_stats", "tpi_window_prefetch",
@@ -106,6 +106,8 @@ def lib() -> C.CDLL:
         l.tpi_shard_layer_prefill.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
                                               C.POINTER(tpi_kv_layer), C.c_int32, C.c_int32, C.c_int,
                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.tpi_set_prefill_concurrency.restype = C.c_int
+        l.tpi_set_prefill_concurrency.argtypes = [C.c_int32]
         l.tpi_star_reduce.restype = C.c_int
         l.tpi_star_reduce.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int64, C.c_void_p,
                                       C.c_void_p, C.c_void_p]
@@ -206,6 +208,10 @@ def tpi_abi_version() -> int:
 
 def tpi_last_error() -> str:
     return lib().tpi_last_error().decode()
+
+
+def tpi_set_prefill_concurrency(n_calls: int) -> None:
+    _check(lib().tpi_set_prefill_concurrency(int(n_calls)))
 
 
 def tpi_workspace_bytes(cfg: tpi_shard_cfg, n_tokens: int = 1) -> int:

@@ -7,6 +7,7 @@
 namespace tpi {
 
 size_t prefill_workspace_bytes(const tpi_shard_cfg *cfg, int32_t n_tokens);
+void prefill_set_concurrency(int n);
 
 // Arguments are already validated (non-null, ranges, dtype == TPI_BF16).
 int prefill_launch(const tpi_shard_cfg *cfg, const tpi_layer_weights *w, const tpi_kv_layer *kv, int32_t pos0,

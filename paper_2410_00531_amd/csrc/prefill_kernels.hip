@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <type_traits>
 
@@ -144,15 +145,17 @@ constexpr int kSwzShift = 1;
 template <int BM, int BN, int NS, int KW, bool SWI = false>
 __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
 {
-    static_assert(!SWI || BN == 128, "the fused activation pairs the two 32-column tiles of a wave");
+    static_assert(!SWI || BN % 128 == 0, "the fused activation pairs neighbouring 32-column tiles of a wave");
     constexpr int BK = 64, NT = 256 * KW;
     constexpr int MI = BM / 64, NI = BN / 64;           // 32x32 tiles per wave along m and n
     constexpr int ACH = BM * (BK / 8) / NT;             // 16-byte chunks per thread, A tile
     constexpr int BCH = BN * (BK / 8) / NT;
     constexpr int STAGE = (BM + BN) * 8;                // chunks per stage
     static_assert(ACH >= 1 && BCH >= 1, "tile too small for the thread count");
-    static_assert(KW == 1 || 8 * NI * 16 * 64 * 4 <= 2 * STAGE * 16, "accumulator exchange must fit the LDS stages");
-    __shared__ uint4 lds[2 * STAGE];
+    constexpr int NP = NI > 2 ? 2 : NI;                 // column tiles per pass of the accumulator exchange
+    static_assert(NI % NP == 0, "whole passes");
+    static_assert(KW == 1 || 8 * NP * 16 * 64 * 4 <= 2 * STAGE * 16, "an exchange pass must fit the LDS stages");
+    extern __shared__ uint4 lds[];                      // 2 * STAGE chunks, sized at launch
 
     const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
     const int wm = wave >> 1, wn = wave & 1;
@@ -174,9 +177,10 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
 #pragma unroll
     for (int i = 0; i < BCH; ++i) {
         if constexpr (SWI) {
-            const int within = (tid + i * NT) >> 3;      // tile column: wave half, gate/up tile, unit
-            const int unit = min((int)blockIdx.x * 64 + (within >> 6) * 32 + (within & 31), g.n_split - 1);
-            pb[i] = ((within & 32) ? g.B1 : g.B0) + (size_t)unit * g.ldb;
+            // tile column -> wave half, pair of 32-column tiles (gate, up), unit within the pair
+            const int within = (tid + i * NT) >> 3, wh = within / (BN / 2), t32 = (within % (BN / 2)) >> 5;
+            const int unit = min((int)blockIdx.x * (BN / 2) + wh * (BN / 4) + (t32 >> 1) * 32 + (within & 31), g.n_split - 1);
+            pb[i] = ((t32 & 1) ? g.B1 : g.B0) + (size_t)unit * g.ldb;
         } else {
             int n = min(n0 + ((tid + i * NT) >> 3), g.N - 1);
             pb[i] = (n < g.n_split) ? g.B0 + (size_t)n * g.ldb : g.B1 + (size_t)(n - g.n_split) * g.ldb;
@@ -284,32 +288,37 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     for (int k0 = k_begin; k0 < k_end; k0 += NS * BK) round(round, std::integral_constant<int, 0>{}, k0);
 
     // KW = 2: the two waves of a pair hold partial sums of the same tiles.  Wave kh hands the other its
-    // partial of row tile 1 - kh through LDS and finishes row tile kh, so all eight waves share the stores.
-    auto give = [&](auto A) {
-        constexpr int a = decltype(A)::value;
+    // partial of row tile 1 - kh through LDS (NP column tiles per pass) and finishes row tile kh, so all
+    // eight waves share the stores.
+    auto give = [&](auto A, auto B0) {
+        constexpr int a = decltype(A)::value, b0 = decltype(B0)::value;
         float *xf = reinterpret_cast<float *>(lds);
 #pragma unroll
-        for (int b = 0; b < NI; ++b)
+        for (int b = 0; b < NP; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) xf[(((wave * 2 + a) * NI + b) * 16 + r) * 64 + lane] = acc[a][b][r];
+            for (int r = 0; r < 16; ++r) xf[(((wave * 2 + a) * NP + b) * 16 + r) * 64 + lane] = acc[a][b0 + b][r];
+    };
+    auto take = [&](auto A, auto B0) {
+        constexpr int a = decltype(A)::value, b0 = decltype(B0)::value;
+        const float *xf = reinterpret_cast<const float *>(lds);
+#pragma unroll
+        for (int b = 0; b < NP; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b0 + b][r] += xf[(((wave * 2 + a) * NP + b) * 16 + r) * 64 + lane];
     };
     // accumulator register r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of its 32x32 tile
-    auto finish = [&](auto A, bool take) {
+    auto finish = [&](auto A) {
         constexpr int a = decltype(A)::value;
-        if (take) {
-            const float *xf = reinterpret_cast<const float *>(lds);
-#pragma unroll
-            for (int b = 0; b < NI; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[a][b][r] += xf[(((wave * 2 + a) * NI + b) * 16 + r) * 64 + lane];
-        }
         if constexpr (SWI) {
-            const int unit = (int)blockIdx.x * 64 + wn * 32 + (lane & 31);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const float gt = acc[a][0][r], up = acc[a][NI - 1][r];
-                if (row < g.M && unit < g.n_split) g.act[(size_t)row * g.n_split + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+            for (int c = 0; c < NI / 2; ++c) {
+                const int unit = (int)blockIdx.x * (BN / 2) + wn * (BN / 4) + c * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const float gt = acc[a][2 * c][r], up = acc[a][2 * c + 1][r];
+                    if (row < g.M && unit < g.n_split) g.act[(size_t)row * g.n_split + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+                }
             }
         } else {
 #pragma unroll
@@ -325,15 +334,26 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     };
     if constexpr (KW == 2) {
         static_assert(MI == 2, "one row tile per wave of a pair");
-        // the loop ended with a barrier: the stages are free
-        if (kh == 0) give(std::integral_constant<int, 1>{});
-        else give(std::integral_constant<int, 0>{});
+        static_assert(NI <= 2 * NP, "at most two passes");
+        // the K loop ended with a barrier: the stages are free
+        if (kh == 0) give(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+        else give(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         __syncthreads();
-        if (kh == 0) finish(std::integral_constant<int, 0>{}, true);
-        else finish(std::integral_constant<int, 1>{}, true);
+        if (kh == 0) take(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        else take(std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{});
+        if constexpr (NI > NP) {
+            __syncthreads();                    // the first pass has been read
+            if (kh == 0) give(std::integral_constant<int, 1>{}, std::integral_constant<int, NP>{});
+            else give(std::integral_constant<int, 0>{}, std::integral_constant<int, NP>{});
+            __syncthreads();
+            if (kh == 0) take(std::integral_constant<int, 0>{}, std::integral_constant<int, NP>{});
+            else take(std::integral_constant<int, 1>{}, std::integral_constant<int, NP>{});
+        }
+        if (kh == 0) finish(std::integral_constant<int, 0>{});
+        else finish(std::integral_constant<int, 1>{});
     } else {
-        finish(std::integral_constant<int, 0>{}, false);
-        if constexpr (MI == 2) finish(std::integral_constant<int, 1>{}, false);
+        finish(std::integral_constant<int, 0>{});
+        if constexpr (MI == 2) finish(std::integral_constant<int, 1>{});
     }
 }
 
@@ -729,10 +749,21 @@ struct GemmPlan {
 };
 
 constexpr int kMaxGemmSplits = 8;
+std::atomic<int> g_concurrency{1};   // prefill calls the caller runs side by side (tpi_set_prefill_concurrency)
 
 GemmPlan plan_gemm(int M, int N, int K, int max_splits)
 {
     GemmPlan p{128, 128, 1, cdiv(K, 64) * 64};
+    // 128x256 tiles move a quarter less through LDS per flop; they are taken once they still occupy three
+    // quarters of the compute units this call can count on (all 256, or its share when the caller has said
+    // that several prefill calls run side by side on different streams).
+    if (max_splits == 1 && M > 64 && N >= 256) {
+        const int share = 256 / std::max(1, g_concurrency.load(std::memory_order_relaxed));
+        if (cdiv(M, 128) * cdiv(N, 256) >= (3 * share) / 4) {
+            p.bn = 256;
+            return p;
+        }
+    }
     if (M <= 64) p.bm = 64;
     int tiles = cdiv(M, p.bm) * cdiv(N, p.bn);
     if (tiles < 128 && max_splits > 1) {
@@ -769,6 +800,28 @@ PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
     return L;
 }
 
+// Launches one instantiation with its LDS size; above 64 KB the kernel has to opt in once per device.
+template <int BM, int BN, int NS, int KW, bool SWI>
+hipError_t launch_gemm_kernel(dim3 grid, const GemmArgs &g, hipStream_t st)
+{
+    constexpr size_t lds = (size_t)2 * (BM + BN) * 8 * 16;
+    auto *kern = k_gemm_bf16_nt<BM, BN, NS, KW, SWI>;
+    if constexpr (lds > 65536) {
+        static bool opted[64] = {};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (!opted[dev]) {
+            e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            opted[dev] = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256 * KW), lds, st, g);
+    return hipGetLastError();
+}
+
 // max_splits > 1: C must have room for that many partial products of M * ldc floats; the number
 // actually written is returned in *n_parts.
 hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t *B1, int n_split, int ldb, float *C,
@@ -779,30 +832,38 @@ hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t 
     GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc, p.k_per_split, (size_t)M * ldc, nullptr};
     ProfScope ps(kStagePrefillGemm, st);
     dim3 grid(cdiv(N, p.bn), cdiv(M, p.bm), p.splits);
-    if (p.bm == 128) hipLaunchKernelGGL((k_gemm_bf16_nt<128, 128, 4, 2>), grid, dim3(512), 0, st, g);
-    else if (p.bn == 128) hipLaunchKernelGGL((k_gemm_bf16_nt<64, 128, 4, 1>), grid, dim3(256), 0, st, g);
-    else hipLaunchKernelGGL((k_gemm_bf16_nt<64, 64, 4, 1>), grid, dim3(256), 0, st, g);
-    return hipGetLastError();
+    if (p.bm == 128 && p.bn == 256) return launch_gemm_kernel<128, 256, 2, 2, false>(grid, g, st);
+    if (p.bm == 128) return launch_gemm_kernel<128, 128, 4, 2, false>(grid, g, st);
+    if (p.bn == 128) return launch_gemm_kernel<64, 128, 4, 1, false>(grid, g, st);
+    return launch_gemm_kernel<64, 64, 4, 1, false>(grid, g, st);
 }
 
 // act[m][j] = bf16(silu(A . gate[j]) * (A . up[j])) in one launch.  False (nothing launched) when the
 // plan for this shape uses 64-column tiles: the caller then multiplies and activates separately.
 bool launch_gemm_swiglu(const bf16_t *A, int lda, const bf16_t *gate, const bf16_t *up, int sl, int ldb, bf16_t *act, int M,
-                        int K, hipStream_t st)
+                        int K, hipStream_t st, hipError_t *err)
 {
     const GemmPlan p = plan_gemm(M, 2 * sl, K, 1);
-    if (p.bn != 128) return false;
+    *err = hipSuccess;
+    if (p.bn < 128) return false;
     GemmArgs g{A, gate, up, nullptr, M, 2 * sl, K, sl, lda, ldb, 0, p.k_per_split, 0, act};
     ProfScope ps(kStagePrefillGemm, st);
+    if (p.bn == 256) {
+        dim3 grid(cdiv(sl, 128), cdiv(M, p.bm), 1);
+        *err = launch_gemm_kernel<128, 256, 2, 2, true>(grid, g, st);
+        return true;
+    }
     dim3 grid(cdiv(sl, 64), cdiv(M, p.bm), 1);
-    if (p.bm == 128) hipLaunchKernelGGL((k_gemm_bf16_nt<128, 128, 4, 2, true>), grid, dim3(512), 0, st, g);
-    else hipLaunchKernelGGL((k_gemm_bf16_nt<64, 128, 4, 1, true>), grid, dim3(256), 0, st, g);
+    if (p.bm == 128) *err = launch_gemm_kernel<128, 128, 4, 2, true>(grid, g, st);
+    else *err = launch_gemm_kernel<64, 128, 4, 1, true>(grid, g, st);
     return true;
 }
 
 }  // namespace
 
 size_t prefill_workspace_bytes(const tpi_shard_cfg *cfg, int32_t n_tokens) { return layout_of(cfg, n_tokens).total; }
+
+void prefill_set_concurrency(int n) { g_concurrency.store(n, std::memory_order_relaxed); }
 
 int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi_kv_layer *kv, int32_t pos0, int32_t n,
                    int phase, const void *h_in, float *partial_out, void *workspace, hipStream_t st)
@@ -887,7 +948,9 @@ int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi
         hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n), dim3(256), 0, st, (const bf16_t *)h_in, (const float *)w->ffn_norm,
                            xn, h, c->rms_eps);
         TPI_LAUNCH_OK();
-        if (!launch_gemm_swiglu(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, act, n, h, st)) {
+        if (launch_gemm_swiglu(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, act, n, h, st, &e)) {
+            if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+        } else {
             e = launch_gemm(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, big, 2 * sl, n, 2 * sl, h, st);
             if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
             const size_t tot = (size_t)n * sl;

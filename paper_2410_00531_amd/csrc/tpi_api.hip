@@ -259,4 +259,12 @@ int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *h
                           (hipStream_t)stream);
 }
 
+int tpi_set_prefill_concurrency(int32_t n_calls)
+{
+    if (n_calls < 1 || n_calls > TPI_MAX_BATCH_SHARDS)
+        return fail(TPI_EINVAL, "n_calls %d outside [1, %d]", n_calls, TPI_MAX_BATCH_SHARDS);
+    prefill_set_concurrency(n_calls);
+    return TPI_OK;
+}
+
 }  // extern "C"

@@ -181,3 +181,12 @@ def test_token_ends_argument_errors_without_a_device():
     assert lib.tpi_next_token(FAKE, 10, 1.0, None, FAKE, None) == B.TPI_EINVAL
     assert lib.tpi_next_token(FAKE, 10, float("nan"), None, FAKE, None) == B.TPI_EINVAL
 
+
+
+def test_prefill_concurrency_hint_arguments():
+    lib = B.lib()
+    assert lib.tpi_set_prefill_concurrency(0) == B.TPI_EINVAL
+    assert lib.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS + 1) == B.TPI_EINVAL
+    assert b"n_calls" in lib.tpi_last_error()
+    assert lib.tpi_set_prefill_concurrency(2) == B.TPI_OK
+    assert lib.tpi_set_prefill_concurrency(1) == B.TPI_OK

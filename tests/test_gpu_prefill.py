@@ -104,6 +104,20 @@ def test_prefill_random_shapes(h, nq, nkv, d, sl, n, pos0):
     _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + int(n % 3), seed=h + n + pos0 + d, attn_scale=4.0)
 
 
+@pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0", [
+    (264, 2, 1, 64, 2776, 300, 0),     # ragged rows, units and K on 128x256 tiles, gate|up with the activation fused
+    (1096, 8, 1, 128, 520, 200, 3),    # output projection and down with 1096 columns: 4 full tiles and a ragged one
+])
+def test_prefill_parity_under_the_concurrency_hint(h, nq, nkv, d, sl, n, pos0):
+    """With the hint that four prefill calls run side by side the GEMM plans take the wide tiles already at
+    these sizes; the results must meet the same tolerance."""
+    B.tpi_set_prefill_concurrency(4)
+    try:
+        _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + 2, seed=h + n, attn_scale=4.0)
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+
+
 def test_prefill_single_token_and_last_slot():
     _run_prefill_case(256, 2, 2, 64, 344, 1, 0, 1, seed=1)
     _run_prefill_case(256, 2, 2, 64, 344, 1, 15, 16, seed=2)
