@@ -168,7 +168,8 @@ int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *h
  * Hint for the prefill's GEMM plans, for callers that run several prefill
  * calls side by side on different streams (the emulated shards of one layer
  * are independent between the all-reduces of Eq. 1 and Eq. 2): each call then
- * sizes its grids for 1/n_calls of the chip, which lets it take wider tiles.
+ * sizes its grids for 1/n_calls of the chip (wider tiles, fewer K splits).
+ * A workspace sized by tpi_workspace_bytes fits every value of the hint.
  * Process-wide, takes effect for later calls, default 1.  The sum of one
  * output element runs over the contraction index in an order that depends on
  * the plan, so results under different hints agree within the bf16 tolerance,

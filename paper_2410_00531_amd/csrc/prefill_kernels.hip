@@ -751,14 +751,17 @@ struct GemmPlan {
 constexpr int kMaxGemmSplits = 8;
 std::atomic<int> g_concurrency{1};   // prefill calls the caller runs side by side (tpi_set_prefill_concurrency)
 
-GemmPlan plan_gemm(int M, int N, int K, int max_splits)
+// share: the compute units the call can count on.  The launches pass the current share; the workspace is
+// sized with the whole chip, which gives the largest number of K splits.
+int current_share() { return 256 / std::max(1, g_concurrency.load(std::memory_order_relaxed)); }
+
+GemmPlan plan_gemm(int M, int N, int K, int max_splits, int share)
 {
     GemmPlan p{128, 128, 1, cdiv(K, 64) * 64};
     // 128x256 tiles move a quarter less through LDS per flop; they are taken once they still occupy three
     // quarters of the compute units this call can count on (all 256, or its share when the caller has said
     // that several prefill calls run side by side on different streams).
     if (max_splits == 1 && M > 64 && N >= 256) {
-        const int share = 256 / std::max(1, g_concurrency.load(std::memory_order_relaxed));
         if (cdiv(M, 128) * cdiv(N, 256) >= (3 * share) / 4) {
             p.bn = 256;
             return p;
@@ -766,9 +769,9 @@ GemmPlan plan_gemm(int M, int N, int K, int max_splits)
     }
     if (M <= 64) p.bm = 64;
     int tiles = cdiv(M, p.bm) * cdiv(N, p.bn);
-    if (tiles < 128 && max_splits > 1) {
+    if (tiles < share / 2 && max_splits > 1) {
         const int ksteps = cdiv(K, 64);
-        int want = std::min(std::min(max_splits, 256 / tiles), std::max(1, ksteps / 4));
+        int want = std::min(std::min(max_splits, share / tiles), std::max(1, ksteps / 4));
         if (want > 1) {
             const int per = cdiv(ksteps, want);
             p.splits = cdiv(ksteps, per);
@@ -790,7 +793,7 @@ PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
     const size_t dq = (size_t)c->n_q_local * c->head_dim, dkv = (size_t)c->n_kv_local * c->head_dim;
     size_t off = 0;
     L.xn = off;  off += align256((size_t)n * c->hidden * 2);
-    const GemmPlan pq = plan_gemm(n, (int)(dq + 2 * dkv), c->hidden, kMaxGemmSplits);
+    const GemmPlan pq = plan_gemm(n, (int)(dq + 2 * dkv), c->hidden, kMaxGemmSplits, 256);
     size_t qkv = (size_t)pq.splits * n * (dq + 2 * dkv) * 4, gu = (size_t)n * 2 * c->ffn_local * 4;
     L.big = off; off += align256(qkv > gu ? qkv : gu);
     L.q = off;   off += align256((size_t)n * dq * 2);
@@ -827,7 +830,7 @@ hipError_t launch_gemm_kernel(dim3 grid, const GemmArgs &g, hipStream_t st)
 hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t *B1, int n_split, int ldb, float *C,
                        int ldc, int M, int N, int K, hipStream_t st, int max_splits = 1, int *n_parts = nullptr)
 {
-    const GemmPlan p = plan_gemm(M, N, K, max_splits);
+    const GemmPlan p = plan_gemm(M, N, K, max_splits, current_share());
     if (n_parts) *n_parts = p.splits;
     GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc, p.k_per_split, (size_t)M * ldc, nullptr};
     ProfScope ps(kStagePrefillGemm, st);
@@ -843,7 +846,7 @@ hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t 
 bool launch_gemm_swiglu(const bf16_t *A, int lda, const bf16_t *gate, const bf16_t *up, int sl, int ldb, bf16_t *act, int M,
                         int K, hipStream_t st, hipError_t *err)
 {
-    const GemmPlan p = plan_gemm(M, 2 * sl, K, 1);
+    const GemmPlan p = plan_gemm(M, 2 * sl, K, 1, current_share());
     *err = hipSuccess;
     if (p.bn < 128) return false;
     GemmArgs g{A, gate, up, nullptr, M, 2 * sl, K, sl, lda, ldb, 0, p.k_per_split, 0, act};
