@@ -165,6 +165,54 @@ def test_prefill_partials_reduce_over_shards():
     assert rel_err(out.cpu().numpy(), O.reduce_f64(refs, x)) <= BF16_TOL
 
 
+def test_prefill_shards_on_two_streams_equal_one_stream_bitwise():
+    """The emulated shards of a layer are independent between the reduces: dealt to two streams (each with a
+    workspace of its own, joined by events before the reduce) they must give the bits of the one-stream run,
+    under the same concurrency hint."""
+    h, nq, nkv, d, sl, n, N = 512, 4, 1, 64, 1280, 300, 4
+    rng = np.random.default_rng(31)
+    cfg = B.make_cfg(h, nq, nkv, d, sl, n, dtype=B.TPI_BF16)
+    xt = _bf16_t(synth.to_bf16_grid(rng.standard_normal((n, h)).astype(np.float32)))
+    shards = []
+    for r in range(N):
+        w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+        wt = {k: (torch.from_numpy(v).cuda() if k.endswith("_norm") else _bf16_t(synth.to_bf16_grid(v))) for k, v in w.items()}
+        Kt = torch.zeros((nkv, n, d), device="cuda", dtype=torch.bfloat16)
+        shards.append((B.make_weights(wt), wt, Kt, torch.zeros_like(Kt)))
+    nws = B.tpi_workspace_bytes(cfg, n) // 4
+
+    def run(streams):
+        main = torch.cuda.current_stream()
+        wss = [torch.full((nws,), float("nan"), device="cuda") for _ in streams]
+        outs = []
+        for phase in (B.TPI_PHASE_ATTN, B.TPI_PHASE_FFN):
+            parts = [torch.empty((n, h), device="cuda") for _ in range(N)]
+            ev = torch.cuda.Event(); ev.record(main)
+            for st in streams:
+                st.wait_event(ev)
+            for r, (W, _, Kt, Vt) in enumerate(shards):
+                st = streams[r % len(streams)]
+                B.tpi_shard_layer_prefill(cfg, W, B.make_kv(Kt, Vt) if phase == B.TPI_PHASE_ATTN else None, 0, n, phase,
+                                          xt, parts[r], wss[r % len(streams)], stream=st)
+            for st in streams:
+                e2 = torch.cuda.Event(); e2.record(st); main.wait_event(e2)
+            out = torch.empty((n, h), device="cuda")
+            B.tpi_star_reduce(parts, None, out)
+            outs.append(out)
+        torch.cuda.synchronize()
+        return outs
+
+    B.tpi_set_prefill_concurrency(2)
+    try:
+        one = run([torch.cuda.current_stream()])
+        two = run([torch.cuda.Stream(), torch.cuda.Stream()])
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+    for a, b in zip(one, two):
+        assert torch.isfinite(a).all()
+        assert torch.equal(a, b)
+
+
 def test_star_reduce_bf16_copy_is_round_to_nearest_even():
     rng = np.random.default_rng(12)
     n, length = 5, 4099
