@@ -165,6 +165,24 @@ int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *h
                             void *stream);
 
 /*
+ * The same prefill phase for n_shards emulated devices in one set of launches
+ * (every kernel takes the shard from a grid dimension; the GEMM plans size
+ * their tiles for the batch).  host_w, host_kv (may be NULL in the FFN
+ * phase), host_partial_out and host_workspace are HOST arrays of n_shards
+ * entries; h_in is shared (it is replicated, Sec. 3.1).  Every shard has the
+ * shape cfg; shards must not share a workspace.  Per shard the results agree
+ * with tpi_shard_layer_prefill within the bf16 tolerance (the plans, and with
+ * them the order of the sums, can differ).
+ * Errors as above, plus TPI_EINVAL for n_shards outside
+ * [1, TPI_MAX_BATCH_SHARDS].
+ */
+int tpi_shards_layer_prefill(const tpi_shard_cfg *cfg, int32_t n_shards,
+                             const tpi_layer_weights *host_w, const tpi_kv_layer *host_kv,
+                             int32_t pos0, int32_t n_tokens, int phase, const void *h_in,
+                             float *const *host_partial_out, void *const *host_workspace,
+                             void *stream);
+
+/*
  * Hint for the prefill's GEMM plans, for callers that run several prefill
  * calls side by side on different streams (the emulated shards of one layer
  * are independent between the all-reduces of Eq. 1 and Eq. 2): each call then

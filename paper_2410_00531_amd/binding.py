@@ -23,7 +23,7 @@ TPI_MAX_REDUCE_RANKS = 64
 TPI_MAX_BATCH_SHARDS = 16
 
 EXPORTED = (
-    "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode", "tpi_set_prefill_concurrency",
+    "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode", "tpi_set_prefill_concurrency", "tpi_shards_layer_prefill",
     "tpi_shard_layer_decode_reduce",
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create",
     "tpi_window_create_blocks", "tpi_window_create_files", "tpi_window_read_stats", "tpi_window_prefetch",
@@ -106,6 +106,10 @@ def lib() -> C.CDLL:
         l.tpi_shard_layer_prefill.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
                                               C.POINTER(tpi_kv_layer), C.c_int32, C.c_int32, C.c_int,
                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.tpi_shards_layer_prefill.restype = C.c_int
+        l.tpi_shards_layer_prefill.argtypes = [C.POINTER(tpi_shard_cfg), C.c_int32, C.POINTER(tpi_layer_weights),
+                                               C.POINTER(tpi_kv_layer), C.c_int32, C.c_int32, C.c_int, C.c_void_p,
+                                               C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]
         l.tpi_set_prefill_concurrency.restype = C.c_int
         l.tpi_set_prefill_concurrency.argtypes = [C.c_int32]
         l.tpi_star_reduce.restype = C.c_int
@@ -251,6 +255,20 @@ def tpi_shards_layer_decode(cfg, weights: Sequence[tpi_layer_weights],
     wsarr = workspaces if isinstance(workspaces, C.Array) else (C.c_void_p * n)(*[_ptr(p) for p in workspaces])
     _check(lib().tpi_shards_layer_decode(C.byref(cfg), n, warr, karr, pos, phase, _ptr(h_in), parr,
                                          wsarr, _stream(stream)))
+
+
+def tpi_shards_layer_prefill(cfg, weights: Sequence[tpi_layer_weights], kvs: Optional[Sequence[tpi_kv_layer]],
+                             pos0: int, n_tokens: int, phase: int, h_in, partial_outs, workspaces, stream=None) -> None:
+    n = len(weights)
+    warr = weights if isinstance(weights, C.Array) else (tpi_layer_weights * n)(*weights)
+    if kvs is None:
+        karr = None
+    else:
+        karr = kvs if isinstance(kvs, C.Array) else (tpi_kv_layer * n)(*kvs)
+    parr = partial_outs if isinstance(partial_outs, C.Array) else (C.c_void_p * n)(*[_ptr(p) for p in partial_outs])
+    wsarr = workspaces if isinstance(workspaces, C.Array) else (C.c_void_p * n)(*[_ptr(p) for p in workspaces])
+    _check(lib().tpi_shards_layer_prefill(C.byref(cfg), n, warr, karr, pos0, n_tokens, phase, _ptr(h_in), parr,
+                                          wsarr, _stream(stream)))
 
 
 def tpi_shard_layer_prefill(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_layer], pos0: int,

@@ -9,9 +9,10 @@ namespace tpi {
 size_t prefill_workspace_bytes(const tpi_shard_cfg *cfg, int32_t n_tokens);
 void prefill_set_concurrency(int n);
 
-// Arguments are already validated (non-null, ranges, dtype == TPI_BF16).
-int prefill_launch(const tpi_shard_cfg *cfg, const tpi_layer_weights *w, const tpi_kv_layer *kv, int32_t pos0,
-                   int32_t n_tokens, int phase, const void *h_in, float *partial_out, void *workspace,
+// n_shards shards of one layer phase (arrays of n_shards entries; kv may be null in the FFN phase).  The
+// configuration, token range, phase and h_in are already validated; the per-shard pointers are checked here.
+int prefill_launch(const tpi_shard_cfg *cfg, int n_shards, const tpi_layer_weights *w, const tpi_kv_layer *kv, int32_t pos0,
+                   int32_t n_tokens, int phase, const void *h_in, float *const *partial_out, void *const *workspace,
                    hipStream_t stream);
 
 }  // namespace tpi

@@ -55,9 +55,24 @@ __device__ __forceinline__ float wsum(float v)
 // ---------------------------------------------------------------------------
 // RMSNorm of n tokens: out[t][k] = bf16( x[t][k] / sqrt(mean_k x^2 + eps) * g[k] ).  One workgroup per token.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_rmsnorm_bf16(const bf16_t *__restrict__ x, const float *__restrict__ g,
-                                                      bf16_t *__restrict__ out, int h, float eps)
+constexpr int kMaxPrefillShards = 16;   // == TPI_MAX_BATCH_SHARDS
+
+// Shards of one batched call differ in their gains and in where the result goes; the input is shared.
+struct NormArgs {
+    const bf16_t *x;
+    int h;
+    float eps;
+    const float *g[kMaxPrefillShards];
+    bf16_t *out[kMaxPrefillShards];
+};
+
+__global__ __launch_bounds__(256) void k_rmsnorm_bf16(NormArgs a)
 {
+    const bf16_t *__restrict__ x = a.x;
+    const float *__restrict__ g = a.g[blockIdx.y];
+    bf16_t *__restrict__ out = a.out[blockIdx.y];
+    const int h = a.h;
+    const float eps = a.eps;
     // the first kKeep * 2048 elements of the row stay in registers between the two passes (rows up to
     // 8192 elements are read once); longer rows read the rest again
     constexpr int kKeep = 4;
@@ -117,17 +132,23 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bf16(const bf16_t *__restrict__
 // An LDS row is 64 elements = 8 chunks of 16 bytes, stored at
 // chunk position (chunk ^ (row & 7)): the fragment reads of 8 consecutive rows then cover all
 // banks without padding.
-// blockIdx.z selects a K range (split-K): split z writes its partial product to C + z * c_split
+// blockIdx.z selects shard and K range (split-K): split z writes its partial product to C + z * c_split
 // and the consumer adds the partials in split order.
-struct GemmArgs {
+struct GemmPtrs {
     const bf16_t *A;
     const bf16_t *B0, *B1;
     float *C;
+    bf16_t *act;              // SWI kernels only: [M][n_split] output of the fused SwiGLU
+};
+
+// One launch covers the shards of a batched call: blockIdx.z = shard * splits + K split.
+struct GemmArgs {
     int M, N, K, n_split;
     int lda, ldb, ldc;
     int k_per_split;          // multiple of 64
+    int splits;
     size_t c_split;           // floats between the partial products of consecutive splits
-    bf16_t *act;              // SWI kernels only: [M][n_split] output of the fused SwiGLU
+    GemmPtrs p[kMaxPrefillShards];
 };
 
 // KW = 2: eight waves; waves 4..7 repeat the 2 x 2 arrangement and take the second half of every
@@ -160,8 +181,10 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
     const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int k_begin = blockIdx.z * g.k_per_split, k_end = min(g.K, k_begin + g.k_per_split);
-    float *C = g.C + (size_t)blockIdx.z * g.c_split;
+    const int shard = blockIdx.z / g.splits, zs = blockIdx.z - shard * g.splits;
+    const GemmPtrs P = g.p[shard];
+    const int k_begin = zs * g.k_per_split, k_end = min(g.K, k_begin + g.k_per_split);
+    float *C = P.C + (size_t)zs * g.c_split;
 
     // this thread's chunks: row c >> 3, chunk c & 7 of the A tile and of the B tile.  Loads are
     // unconditional (straight-line code keeps the ring's loads in flight across K-steps): rows past
@@ -172,7 +195,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
         int m = min(m0 + ((tid + i * NT) >> 3), g.M - 1);
-        pa[i] = g.A + (size_t)m * g.lda;
+        pa[i] = P.A + (size_t)m * g.lda;
     }
 #pragma unroll
     for (int i = 0; i < BCH; ++i) {
@@ -180,10 +203,10 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
             // tile column -> wave half, pair of 32-column tiles (gate, up), unit within the pair
             const int within = (tid + i * NT) >> 3, wh = within / (BN / 2), t32 = (within % (BN / 2)) >> 5;
             const int unit = min((int)blockIdx.x * (BN / 2) + wh * (BN / 4) + (t32 >> 1) * 32 + (within & 31), g.n_split - 1);
-            pb[i] = ((t32 & 1) ? g.B1 : g.B0) + (size_t)unit * g.ldb;
+            pb[i] = ((t32 & 1) ? P.B1 : P.B0) + (size_t)unit * g.ldb;
         } else {
             int n = min(n0 + ((tid + i * NT) >> 3), g.N - 1);
-            pb[i] = (n < g.n_split) ? g.B0 + (size_t)n * g.ldb : g.B1 + (size_t)(n - g.n_split) * g.ldb;
+            pb[i] = (n < g.n_split) ? P.B0 + (size_t)n * g.ldb : P.B1 + (size_t)(n - g.n_split) * g.ldb;
         }
     }
     // (row * 8 + chunk) -> swizzled LDS position; row & 7 == (tid >> 3) & 7 for every i
@@ -317,7 +340,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
                 for (int r = 0; r < 16; ++r) {
                     int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     const float gt = acc[a][2 * c][r], up = acc[a][2 * c + 1][r];
-                    if (row < g.M && unit < g.n_split) g.act[(size_t)row * g.n_split + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+                    if (row < g.M && unit < g.n_split) P.act[(size_t)row * g.n_split + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
                 }
             }
         } else {
@@ -364,11 +387,25 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
 // the nkv value heads.  Query and key slots rotate element pair (e, e + d/2) at position pos0 + token (angle
 // in fp64); q goes out as bf16 [n][nq*d], K and V into cache slot pos0 + token.
 // The QKV product arrives as n_parts split-K partials, part_stride floats apart, added in split order.
-__global__ __launch_bounds__(256) void k_rope_scatter(const float *__restrict__ qkv, int n_parts, size_t part_stride,
-                                                      bf16_t *__restrict__ q_out, bf16_t *__restrict__ Kc,
-                                                      bf16_t *__restrict__ Vc, int n, int nq, int nkv, int d,
-                                                      int max_seq, int pos0, double log2_base)
+// blockIdx.y selects the shard of a batched call.
+struct RopeArgs {
+    int n_parts;
+    size_t part_stride;
+    int n, nq, nkv, d, max_seq, pos0;
+    double log2_base;
+    const float *qkv[kMaxPrefillShards];
+    bf16_t *q_out[kMaxPrefillShards], *Kc[kMaxPrefillShards], *Vc[kMaxPrefillShards];
+};
+
+__global__ __launch_bounds__(256) void k_rope_scatter(RopeArgs a)
 {
+    const float *__restrict__ qkv = a.qkv[blockIdx.y];
+    bf16_t *__restrict__ q_out = a.q_out[blockIdx.y];
+    bf16_t *__restrict__ Kc = a.Kc[blockIdx.y];
+    bf16_t *__restrict__ Vc = a.Vc[blockIdx.y];
+    const int n_parts = a.n_parts, n = a.n, nq = a.nq, nkv = a.nkv, d = a.d, max_seq = a.max_seq, pos0 = a.pos0;
+    const size_t part_stride = a.part_stride;
+    const double log2_base = a.log2_base;
     const int half = d / 2, nh = nq + 2 * nkv;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= n * nh * half) return;
@@ -535,11 +572,21 @@ __global__ __launch_bounds__(256) void k_prefill_attn(const bf16_t *__restrict__
 // (cast to bf16), no data movement; V^T is read from a per-wave LDS tile laid out
 // [key / 4][e][key % 4], in the key order the score registers hold (the contraction index may be
 // permuted as long as both operands agree).
+// blockIdx.z selects the shard of a batched call.
+struct AttnArgs {
+    int n, nq, nkv, max_seq, pos0;
+    const bf16_t *q[kMaxPrefillShards], *Kc[kMaxPrefillShards], *Vc[kMaxPrefillShards];
+    bf16_t *o[kMaxPrefillShards];
+};
+
 template <int D>
-__global__ __launch_bounds__(256) void k_prefill_attn_mfma(const bf16_t *__restrict__ q, const bf16_t *__restrict__ Kc,
-                                                           const bf16_t *__restrict__ Vc, bf16_t *__restrict__ o, int n,
-                                                           int nq, int nkv, int max_seq, int pos0)
+__global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
 {
+    const bf16_t *__restrict__ q = a.q[blockIdx.z];
+    const bf16_t *__restrict__ Kc = a.Kc[blockIdx.z];
+    const bf16_t *__restrict__ Vc = a.Vc[blockIdx.z];
+    bf16_t *__restrict__ o = a.o[blockIdx.z];
+    const int n = a.n, nq = a.nq, nkv = a.nkv, max_seq = a.max_seq, pos0 = a.pos0;
     constexpr int ET = D / 32, KS = D / 16, TK = 32;
     constexpr int VT = (TK / 4) * D * 4;                          // bf16 elements of one V tile
     constexpr int MERGE = 3 * ET * 16 * 64;                       // floats: three foreign shares of every output tile
@@ -779,11 +826,11 @@ GemmPlan plan_gemm(int M, int N, int K, int max_splits, int share)
             return p;
         }
     }
-    if (tiles < 128 && p.bm == 128) {
+    if (tiles < share / 2 && p.bm == 128) {
         p.bm = 64;
         tiles = cdiv(M, 64) * cdiv(N, 128);
     }
-    if (tiles < 128) p.bn = 64;
+    if (tiles < share / 2) p.bn = 64;
     return p;
 }
 
@@ -827,36 +874,44 @@ hipError_t launch_gemm_kernel(dim3 grid, const GemmArgs &g, hipStream_t st)
 
 // max_splits > 1: C must have room for that many partial products of M * ldc floats; the number
 // actually written is returned in *n_parts.
-hipError_t launch_gemm(const bf16_t *A, int lda, const bf16_t *B0, const bf16_t *B1, int n_split, int ldb, float *C,
-                       int ldc, int M, int N, int K, hipStream_t st, int max_splits = 1, int *n_parts = nullptr)
+// One GEMM launch for the S shards of a batched call (ptrs[s].C is the shard's output; with max_splits > 1 it
+// must have room for that many partial products of M * ldc floats; the number written is returned in *n_parts).
+hipError_t launch_gemm(const GemmPtrs *ptrs, int S, int lda, int n_split, int ldb, int ldc, int M, int N, int K,
+                       hipStream_t st, int max_splits = 1, int *n_parts = nullptr)
 {
-    const GemmPlan p = plan_gemm(M, N, K, max_splits, current_share());
+    const GemmPlan p = plan_gemm(M, N, K, max_splits, std::max(1, current_share() / S));
     if (n_parts) *n_parts = p.splits;
-    GemmArgs g{A, B0, B1, C, M, N, K, n_split, lda, ldb, ldc, p.k_per_split, (size_t)M * ldc, nullptr};
+    GemmArgs g{};
+    g.M = M; g.N = N; g.K = K; g.n_split = n_split; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+    g.k_per_split = p.k_per_split; g.splits = p.splits; g.c_split = (size_t)M * ldc;
+    for (int s = 0; s < S; ++s) g.p[s] = ptrs[s];
     ProfScope ps(kStagePrefillGemm, st);
-    dim3 grid(cdiv(N, p.bn), cdiv(M, p.bm), p.splits);
+    dim3 grid(cdiv(N, p.bn), cdiv(M, p.bm), p.splits * S);
     if (p.bm == 128 && p.bn == 256) return launch_gemm_kernel<128, 256, 2, 2, false>(grid, g, st);
     if (p.bm == 128) return launch_gemm_kernel<128, 128, 4, 2, false>(grid, g, st);
     if (p.bn == 128) return launch_gemm_kernel<64, 128, 4, 1, false>(grid, g, st);
     return launch_gemm_kernel<64, 64, 4, 1, false>(grid, g, st);
 }
 
-// act[m][j] = bf16(silu(A . gate[j]) * (A . up[j])) in one launch.  False (nothing launched) when the
-// plan for this shape uses 64-column tiles: the caller then multiplies and activates separately.
-bool launch_gemm_swiglu(const bf16_t *A, int lda, const bf16_t *gate, const bf16_t *up, int sl, int ldb, bf16_t *act, int M,
-                        int K, hipStream_t st, hipError_t *err)
+// act[m][j] = bf16(silu(A . gate[j]) * (A . up[j])) in one launch (B0 = gate, B1 = up, act set, C unused).  False
+// (nothing launched) when the plan for this shape uses 64-column tiles: the caller then multiplies and
+// activates separately.
+bool launch_gemm_swiglu(const GemmPtrs *ptrs, int S, int lda, int sl, int ldb, int M, int K, hipStream_t st, hipError_t *err)
 {
-    const GemmPlan p = plan_gemm(M, 2 * sl, K, 1, current_share());
+    const GemmPlan p = plan_gemm(M, 2 * sl, K, 1, std::max(1, current_share() / S));
     *err = hipSuccess;
     if (p.bn < 128) return false;
-    GemmArgs g{A, gate, up, nullptr, M, 2 * sl, K, sl, lda, ldb, 0, p.k_per_split, 0, act};
+    GemmArgs g{};
+    g.M = M; g.N = 2 * sl; g.K = K; g.n_split = sl; g.lda = lda; g.ldb = ldb; g.ldc = 0;
+    g.k_per_split = p.k_per_split; g.splits = 1; g.c_split = 0;
+    for (int s = 0; s < S; ++s) g.p[s] = ptrs[s];
     ProfScope ps(kStagePrefillGemm, st);
     if (p.bn == 256) {
-        dim3 grid(cdiv(sl, 128), cdiv(M, p.bm), 1);
+        dim3 grid(cdiv(sl, 128), cdiv(M, p.bm), S);
         *err = launch_gemm_kernel<128, 256, 2, 2, true>(grid, g, st);
         return true;
     }
-    dim3 grid(cdiv(sl, 64), cdiv(M, p.bm), 1);
+    dim3 grid(cdiv(sl, 64), cdiv(M, p.bm), S);
     if (p.bm == 128) *err = launch_gemm_kernel<128, 128, 4, 2, true>(grid, g, st);
     else *err = launch_gemm_kernel<64, 128, 4, 1, true>(grid, g, st);
     return true;
@@ -868,53 +923,78 @@ size_t prefill_workspace_bytes(const tpi_shard_cfg *cfg, int32_t n_tokens) { ret
 
 void prefill_set_concurrency(int n) { g_concurrency.store(n, std::memory_order_relaxed); }
 
-int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi_kv_layer *kv, int32_t pos0, int32_t n,
-                   int phase, const void *h_in, float *partial_out, void *workspace, hipStream_t st)
+// S shards of one layer phase in one set of launches: every kernel takes the shard from a grid dimension.
+int prefill_launch(const tpi_shard_cfg *c, int S, const tpi_layer_weights *w, const tpi_kv_layer *kv, int32_t pos0, int32_t n,
+                   int phase, const void *h_in, float *const *partial_out, void *const *workspace, hipStream_t st)
 {
     const int h = c->hidden, d = c->head_dim, nq = c->n_q_local, nkv = c->n_kv_local, sl = c->ffn_local;
     const int dq = nq * d, dkv = nkv * d;
     auto al = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
-    if (!al(h_in) || !al(partial_out) || !al(workspace)) return fail(TPI_EUNSUPPORTED, "pointer not 16-byte aligned");
+    if (S < 1 || S > kMaxPrefillShards) return fail(TPI_EINVAL, "n_shards %d outside [1, %d]", S, kMaxPrefillShards);
+    if (!al(h_in)) return fail(TPI_EUNSUPPORTED, "pointer not 16-byte aligned");
     const PrefillLayout L = layout_of(c, n);
-    char *ws = static_cast<char *>(workspace);
-    bf16_t *xn = reinterpret_cast<bf16_t *>(ws + L.xn);
-    float *big = reinterpret_cast<float *>(ws + L.big);
-    bf16_t *qb = reinterpret_cast<bf16_t *>(ws + L.q);
-    bf16_t *ob = reinterpret_cast<bf16_t *>(ws + L.o);
-    bf16_t *act = reinterpret_cast<bf16_t *>(ws + L.act);
+    bf16_t *xn[kMaxPrefillShards], *qb[kMaxPrefillShards], *ob[kMaxPrefillShards], *act[kMaxPrefillShards];
+    float *big[kMaxPrefillShards];
+    for (int s = 0; s < S; ++s) {
+        if (!partial_out[s] || !workspace[s]) return fail(TPI_EINVAL, "shard %d: null output or workspace", s);
+        if (!al(partial_out[s]) || !al(workspace[s])) return fail(TPI_EUNSUPPORTED, "shard %d: pointer not 16-byte aligned", s);
+        char *ws = static_cast<char *>(workspace[s]);
+        xn[s] = reinterpret_cast<bf16_t *>(ws + L.xn);
+        big[s] = reinterpret_cast<float *>(ws + L.big);
+        qb[s] = reinterpret_cast<bf16_t *>(ws + L.q);
+        ob[s] = reinterpret_cast<bf16_t *>(ws + L.o);
+        act[s] = reinterpret_cast<bf16_t *>(ws + L.act);
+    }
     hipError_t e = hipSuccess;
 #define TPI_LAUNCH_OK()                                                                         \
     do {                                                                                        \
         e = hipGetLastError();                                                                  \
         if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e)); \
     } while (0)
+#define TPI_GEMM_OK()                                                                           \
+    do {                                                                                        \
+        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e)); \
+    } while (0)
+
+    NormArgs na{};
+    na.x = (const bf16_t *)h_in; na.h = h; na.eps = c->rms_eps;
+    GemmPtrs gp[kMaxPrefillShards];
 
     if (phase == TPI_PHASE_ATTN) {
-        if (!w->attn_norm || !w->w_qkv || !w->w_o) return fail(TPI_EINVAL, "null attention weight pointer");
-        if (!al(w->attn_norm) || !al(w->w_qkv) || !al(w->w_o) || !al(kv->k) || !al(kv->v))
-            return fail(TPI_EUNSUPPORTED, "pointer not 16-byte aligned");
+        for (int s = 0; s < S; ++s) {
+            if (!w[s].attn_norm || !w[s].w_qkv || !w[s].w_o || !kv[s].k || !kv[s].v)
+                return fail(TPI_EINVAL, "shard %d: null attention weight or cache pointer", s);
+            if (!al(w[s].attn_norm) || !al(w[s].w_qkv) || !al(w[s].w_o) || !al(kv[s].k) || !al(kv[s].v))
+                return fail(TPI_EUNSUPPORTED, "shard %d: pointer not 16-byte aligned", s);
+            na.g[s] = (const float *)w[s].attn_norm; na.out[s] = xn[s];
+        }
         if (d > 256) return fail(TPI_EUNSUPPORTED, "head_dim %d > 256", d);
         const int G = nq / nkv;
         if (G > 64) return fail(TPI_EUNSUPPORTED, "more than 64 query heads per KV head");
-        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n), dim3(256), 0, st, (const bf16_t *)h_in, (const float *)w->attn_norm,
-                           xn, h, c->rms_eps);
+        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n, S), dim3(256), 0, st, na);
         TPI_LAUNCH_OK();
         int qkv_parts = 1;
-        e = launch_gemm(xn, h, (const bf16_t *)w->w_qkv, (const bf16_t *)w->w_qkv, dq + 2 * dkv, h, big, dq + 2 * dkv, n,
-                        dq + 2 * dkv, h, st, kMaxGemmSplits, &qkv_parts);
-        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+        for (int s = 0; s < S; ++s) gp[s] = GemmPtrs{xn[s], (const bf16_t *)w[s].w_qkv, (const bf16_t *)w[s].w_qkv, big[s], nullptr};
+        e = launch_gemm(gp, S, h, dq + 2 * dkv, h, dq + 2 * dkv, n, dq + 2 * dkv, h, st, kMaxGemmSplits, &qkv_parts);
+        TPI_GEMM_OK();
+        RopeArgs ra{};
+        ra.n_parts = qkv_parts; ra.part_stride = (size_t)n * (dq + 2 * dkv);
+        ra.n = n; ra.nq = nq; ra.nkv = nkv; ra.d = d; ra.max_seq = c->max_seq; ra.pos0 = pos0;
+        ra.log2_base = std::log2((double)c->rope_base);
+        for (int s = 0; s < S; ++s) { ra.qkv[s] = big[s]; ra.q_out[s] = qb[s]; ra.Kc[s] = (bf16_t *)kv[s].k; ra.Vc[s] = (bf16_t *)kv[s].v; }
         const int nthr = n * (nq + 2 * nkv) * (d / 2);
-        hipLaunchKernelGGL(k_rope_scatter, dim3((nthr + 255) / 256), dim3(256), 0, st, big, qkv_parts,
-                           (size_t)n * (dq + 2 * dkv), qb, (bf16_t *)kv->k,
-                           (bf16_t *)kv->v, n, nq, nkv, d, c->max_seq, pos0, std::log2((double)c->rope_base));
+        hipLaunchKernelGGL(k_rope_scatter, dim3((nthr + 255) / 256, S), dim3(256), 0, st, ra);
         TPI_LAUNCH_OK();
         if (d % 32 == 0 && d <= 128) {
-            dim3 grid((n * G + 31) / 32, nkv);
+            AttnArgs aa{};
+            aa.n = n; aa.nq = nq; aa.nkv = nkv; aa.max_seq = c->max_seq; aa.pos0 = pos0;
+            for (int s = 0; s < S; ++s) { aa.q[s] = qb[s]; aa.Kc[s] = (const bf16_t *)kv[s].k; aa.Vc[s] = (const bf16_t *)kv[s].v; aa.o[s] = ob[s]; }
+            dim3 grid((n * G + 31) / 32, nkv, S);
             switch (d) {
-            case 32: hipLaunchKernelGGL((k_prefill_attn_mfma<32>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
-            case 64: hipLaunchKernelGGL((k_prefill_attn_mfma<64>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
-            case 96: hipLaunchKernelGGL((k_prefill_attn_mfma<96>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
-            default: hipLaunchKernelGGL((k_prefill_attn_mfma<128>), grid, dim3(256), 0, st, qb, (const bf16_t *)kv->k, (const bf16_t *)kv->v, ob, n, nq, nkv, c->max_seq, pos0); break;
+            case 32: hipLaunchKernelGGL((k_prefill_attn_mfma<32>), grid, dim3(256), 0, st, aa); break;
+            case 64: hipLaunchKernelGGL((k_prefill_attn_mfma<64>), grid, dim3(256), 0, st, aa); break;
+            case 96: hipLaunchKernelGGL((k_prefill_attn_mfma<96>), grid, dim3(256), 0, st, aa); break;
+            default: hipLaunchKernelGGL((k_prefill_attn_mfma<128>), grid, dim3(256), 0, st, aa); break;
             }
             TPI_LAUNCH_OK();
         } else {
@@ -931,39 +1011,49 @@ int prefill_launch(const tpi_shard_cfg *c, const tpi_layer_weights *w, const tpi
                               : hipFuncSetAttribute((const void *)k_prefill_attn<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
                 if (e != hipSuccess) return fail(TPI_ERUNTIME, "hipFuncSetAttribute: %s", hipGetErrorString(e));
             }
-            if (d <= 64) {
-                hipLaunchKernelGGL((k_prefill_attn<64>), grid, dim3(256), lds, st, qb, (const bf16_t *)kv->k,
-                                   (const bf16_t *)kv->v, ob, n, nq, nkv, d, c->max_seq, pos0, QT);
-            } else if (d <= 128) {
-                hipLaunchKernelGGL((k_prefill_attn<128>), grid, dim3(256), lds, st, qb, (const bf16_t *)kv->k,
-                                   (const bf16_t *)kv->v, ob, n, nq, nkv, d, c->max_seq, pos0, QT);
-            } else {
-                return fail(TPI_EUNSUPPORTED, "prefill attention is built for head_dim <= 128");
+            if (d > 128) return fail(TPI_EUNSUPPORTED, "prefill attention is built for head_dim <= 128");
+            for (int s = 0; s < S; ++s) {                  // the vector-ALU attention takes one shard per launch
+                if (d <= 64) {
+                    hipLaunchKernelGGL((k_prefill_attn<64>), grid, dim3(256), lds, st, qb[s], (const bf16_t *)kv[s].k,
+                                       (const bf16_t *)kv[s].v, ob[s], n, nq, nkv, d, c->max_seq, pos0, QT);
+                } else {
+                    hipLaunchKernelGGL((k_prefill_attn<128>), grid, dim3(256), lds, st, qb[s], (const bf16_t *)kv[s].k,
+                                       (const bf16_t *)kv[s].v, ob[s], n, nq, nkv, d, c->max_seq, pos0, QT);
+                }
+                TPI_LAUNCH_OK();
             }
-            TPI_LAUNCH_OK();
         }
-        e = launch_gemm(ob, dq, (const bf16_t *)w->w_o, (const bf16_t *)w->w_o, h, dq, partial_out, h, n, h, dq, st);
-        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+        for (int s = 0; s < S; ++s) gp[s] = GemmPtrs{ob[s], (const bf16_t *)w[s].w_o, (const bf16_t *)w[s].w_o, partial_out[s], nullptr};
+        e = launch_gemm(gp, S, dq, h, dq, h, n, h, dq, st);
+        TPI_GEMM_OK();
     } else {
-        if (!w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down) return fail(TPI_EINVAL, "null FFN weight pointer");
-        if (!al(w->ffn_norm) || !al(w->w_gate) || !al(w->w_up) || !al(w->w_down))
-            return fail(TPI_EUNSUPPORTED, "pointer not 16-byte aligned");
-        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n), dim3(256), 0, st, (const bf16_t *)h_in, (const float *)w->ffn_norm,
-                           xn, h, c->rms_eps);
-        TPI_LAUNCH_OK();
-        if (launch_gemm_swiglu(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, act, n, h, st, &e)) {
-            if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
-        } else {
-            e = launch_gemm(xn, h, (const bf16_t *)w->w_gate, (const bf16_t *)w->w_up, sl, h, big, 2 * sl, n, 2 * sl, h, st);
-            if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
-            const size_t tot = (size_t)n * sl;
-            hipLaunchKernelGGL(k_swiglu, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, big, act, n, sl);
+        for (int s = 0; s < S; ++s) {
+            if (!w[s].ffn_norm || !w[s].w_gate || !w[s].w_up || !w[s].w_down)
+                return fail(TPI_EINVAL, "shard %d: null FFN weight pointer", s);
+            if (!al(w[s].ffn_norm) || !al(w[s].w_gate) || !al(w[s].w_up) || !al(w[s].w_down))
+                return fail(TPI_EUNSUPPORTED, "shard %d: pointer not 16-byte aligned", s);
+            na.g[s] = (const float *)w[s].ffn_norm; na.out[s] = xn[s];
         }
+        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n, S), dim3(256), 0, st, na);
         TPI_LAUNCH_OK();
-        e = launch_gemm(act, sl, (const bf16_t *)w->w_down, (const bf16_t *)w->w_down, h, sl, partial_out, h, n, h, sl, st);
-        if (e != hipSuccess) return fail(TPI_ERUNTIME, "kernel launch failed: %s", hipGetErrorString(e));
+        for (int s = 0; s < S; ++s) gp[s] = GemmPtrs{xn[s], (const bf16_t *)w[s].w_gate, (const bf16_t *)w[s].w_up, big[s], act[s]};
+        if (launch_gemm_swiglu(gp, S, h, sl, h, n, h, st, &e)) {
+            TPI_GEMM_OK();
+        } else {
+            e = launch_gemm(gp, S, h, sl, h, 2 * sl, n, 2 * sl, h, st);
+            TPI_GEMM_OK();
+            const size_t tot = (size_t)n * sl;
+            for (int s = 0; s < S; ++s) {
+                hipLaunchKernelGGL(k_swiglu, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, big[s], act[s], n, sl);
+                TPI_LAUNCH_OK();
+            }
+        }
+        for (int s = 0; s < S; ++s) gp[s] = GemmPtrs{act[s], (const bf16_t *)w[s].w_down, (const bf16_t *)w[s].w_down, partial_out[s], nullptr};
+        e = launch_gemm(gp, S, sl, h, sl, h, n, h, sl, st);
+        TPI_GEMM_OK();
     }
 #undef TPI_LAUNCH_OK
+#undef TPI_GEMM_OK
     return TPI_OK;
 }
 

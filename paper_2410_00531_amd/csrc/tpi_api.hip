@@ -240,23 +240,41 @@ int tpi_star_reduce_bf16(const float *const *host_partials, int32_t n, int64_t l
     return star_reduce_common(host_partials, n, len, residual, out, out_bf16, stream);
 }
 
-int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w, const tpi_kv_layer *host_kv,
-                            int32_t pos0, int32_t n_tokens, int phase, const void *h_in, float *partial_out,
-                            void *workspace, void *stream)
+static int prefill_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_layer_weights *host_w,
+                          const tpi_kv_layer *host_kv, int32_t pos0, int32_t n_tokens, int phase, const void *h_in,
+                          float *const *partial_out, void *const *workspace, void *stream)
 {
     int rc = check_cfg(cfg);
     if (rc) return rc;
     if (phase != TPI_PHASE_ATTN && phase != TPI_PHASE_FFN) return fail(TPI_EINVAL, "unknown phase %d", phase);
+    if (n_shards < 1) return fail(TPI_EINVAL, "n_shards %d < 1", n_shards);
+    if (n_shards > TPI_MAX_BATCH_SHARDS) return fail(TPI_EINVAL, "n_shards %d > %d", n_shards, TPI_MAX_BATCH_SHARDS);
     if (!host_w || !h_in || !partial_out || !workspace) return fail(TPI_EINVAL, "null argument");
-    if (phase == TPI_PHASE_ATTN && (!host_kv || !host_kv->k || !host_kv->v))
-        return fail(TPI_EINVAL, "kv is null in the attention phase");
+    if (phase == TPI_PHASE_ATTN && !host_kv) return fail(TPI_EINVAL, "kv is null in the attention phase");
     if (n_tokens < 1) return fail(TPI_EINVAL, "n_tokens %d < 1", n_tokens);
     if (pos0 < 0 || (int64_t)pos0 + n_tokens > cfg->max_seq)
         return fail(TPI_EINVAL, "positions %d..%lld outside [0, max_seq %d)", pos0, (long long)pos0 + n_tokens - 1,
                     cfg->max_seq);
     if (cfg->dtype != TPI_BF16) return fail(TPI_EUNSUPPORTED, "prefill is built for bf16 only");
-    return prefill_launch(cfg, host_w, host_kv, pos0, n_tokens, phase, h_in, partial_out, workspace,
+    return prefill_launch(cfg, n_shards, host_w, host_kv, pos0, n_tokens, phase, h_in, partial_out, workspace,
                           (hipStream_t)stream);
+}
+
+int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w, const tpi_kv_layer *host_kv,
+                            int32_t pos0, int32_t n_tokens, int phase, const void *h_in, float *partial_out,
+                            void *workspace, void *stream)
+{
+    float *po[1] = {partial_out};
+    void *ws[1] = {workspace};
+    return prefill_common(cfg, 1, host_w, host_kv, pos0, n_tokens, phase, h_in, po, ws, stream);
+}
+
+int tpi_shards_layer_prefill(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_layer_weights *host_w,
+                             const tpi_kv_layer *host_kv, int32_t pos0, int32_t n_tokens, int phase, const void *h_in,
+                             float *const *host_partial_out, void *const *host_workspace, void *stream)
+{
+    return prefill_common(cfg, n_shards, host_w, host_kv, pos0, n_tokens, phase, h_in, host_partial_out, host_workspace,
+                          stream);
 }
 
 int tpi_set_prefill_concurrency(int32_t n_calls)

@@ -165,6 +165,59 @@ def test_prefill_partials_reduce_over_shards():
     assert rel_err(out.cpu().numpy(), O.reduce_f64(refs, x)) <= BF16_TOL
 
 
+@pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0,N", [
+    (512, 4, 1, 64, 1280, 300, 0, 4),      # wide tiles under the batch, gate|up fused
+    (264, 2, 2, 32, 72, 70, 5, 3),         # ragged everything, small tiles, split-K QKV
+    (192, 2, 1, 48, 64, 33, 0, 2),         # head_dim 48: the vector-ALU attention, one shard per launch
+    (256, 2, 1, 64, 128, 40, 2, B.TPI_MAX_BATCH_SHARDS),
+])
+def test_prefill_batched_call_matches_per_shard_calls_and_oracle(h, nq, nkv, d, sl, n, pos0, N):
+    """tpi_shards_layer_prefill: all shards of a layer phase in one set of launches.  Per shard the result must
+    agree with the single-shard call (the plans may differ: tolerance, not bits), the cache slots written must be
+    the same set, and shard 0 is checked against the oracle."""
+    rng = np.random.default_rng(h + n + N)
+    max_seq = pos0 + n + 1
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq, dtype=B.TPI_BF16)
+    oc = O.ShardCfg(h, nq, nkv, d, sl, max_seq)
+    x = synth.to_bf16_grid(rng.standard_normal((n, h)).astype(np.float32))
+    xt = _bf16_t(x)
+    nws = B.tpi_workspace_bytes(cfg, n) // 4
+    sh = []
+    for r in range(N):
+        w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+        wb = {k: (v if k.endswith("_norm") else synth.to_bf16_grid(v)) for k, v in w.items()}
+        wt = {k: (torch.from_numpy(v).cuda() if k.endswith("_norm") else _bf16_t(v)) for k, v in wb.items()}
+        K = np.full((nkv, max_seq, d), 123.0, np.float32); V = K.copy()
+        K[:, :pos0] = synth.to_bf16_grid(rng.standard_normal((nkv, pos0, d)).astype(np.float32))
+        V[:, :pos0] = synth.to_bf16_grid(rng.standard_normal((nkv, pos0, d)).astype(np.float32))
+        sh.append(dict(wb=wb, wt=wt, W=B.make_weights(wt), K=K, V=V,
+                       Ka=_bf16_t(K), Va=_bf16_t(V), Kb=_bf16_t(K), Vb=_bf16_t(V),
+                       wsa=torch.full((nws,), float("nan"), device="cuda"), wsb=torch.full((nws,), float("nan"), device="cuda")))
+    for phase in (B.TPI_PHASE_ATTN, B.TPI_PHASE_FFN):
+        pa = [torch.empty((n, h), device="cuda") for _ in range(N)]
+        pb = [torch.empty((n, h), device="cuda") for _ in range(N)]
+        attn = phase == B.TPI_PHASE_ATTN
+        B.tpi_shards_layer_prefill(cfg, [s_["W"] for s_ in sh], [B.make_kv(s_["Ka"], s_["Va"]) for s_ in sh] if attn else None,
+                                   pos0, n, phase, xt, pa, [s_["wsa"] for s_ in sh])
+        for r, s_ in enumerate(sh):
+            B.tpi_shard_layer_prefill(cfg, s_["W"], B.make_kv(s_["Kb"], s_["Vb"]) if attn else None, pos0, n, phase, xt,
+                                      pb[r], s_["wsb"])
+        torch.cuda.synchronize()
+        for r, s_ in enumerate(sh):
+            assert rel_err(pa[r].cpu().numpy(), pb[r].cpu().numpy()) <= 2e-3, f"shard {r}"
+            if attn:
+                ka, kb = s_["Ka"].float().cpu().numpy(), s_["Kb"].float().cpu().numpy()
+                assert np.array_equal(ka != s_["K"], kb != s_["K"])          # the same slots written
+                assert rel_err(ka[:, pos0:pos0 + n], kb[:, pos0:pos0 + n]) <= 1e-2
+                assert rel_err(s_["Va"].float().cpu().numpy()[:, pos0:pos0 + n], s_["Vb"].float().cpu().numpy()[:, pos0:pos0 + n]) <= 1e-2
+        w0 = sh[0]["wb"]
+        if attn:
+            ref = O.attn_block(oc, w0["attn_norm"], w0["w_qkv"], w0["w_o"], sh[0]["K"].copy(), sh[0]["V"].copy(), pos0, x)
+        else:
+            ref = O.ffn_block(oc, w0["ffn_norm"], w0["w_gate"], w0["w_up"], w0["w_down"], x)
+        assert rel_err(pa[0].cpu().numpy(), ref) <= BF16_TOL
+
+
 def test_prefill_shards_on_two_streams_equal_one_stream_bitwise():
     """The emulated shards of a layer are independent between the reduces: dealt to two streams (each with a
     workspace of its own, joined by events before the reduce) they must give the bits of the one-stream run,
