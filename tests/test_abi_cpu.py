@@ -107,6 +107,21 @@ def test_star_reduce_and_prefill_argument_errors():
     assert _code(pre, cfg, -1, 5) == B.TPI_EINVAL
     assert _code(pre, cfg, 0, 0) == B.TPI_EINVAL
     assert _code(pre, B.make_cfg(256, 2, 2, 64, 344, 24), 0, 4) == B.TPI_EUNSUPPORTED   # fp32 prefill
+    # per-shard pointers are checked before anything is queued
+    assert _code(B.tpi_shard_layer_prefill, cfg, _w(), B.tpi_kv_layer(FAKE, None), 0, 4, B.TPI_PHASE_ATTN, FAKE, FAKE,
+                 FAKE, stream=0) == B.TPI_EINVAL
+    assert _code(B.tpi_shard_layer_prefill, cfg, _w(), kv, 0, 4, B.TPI_PHASE_ATTN, FAKE, None, FAKE, stream=0) == B.TPI_EINVAL
+    assert _code(B.tpi_shard_layer_prefill, cfg, _w(), kv, 0, 4, B.TPI_PHASE_ATTN, FAKE, FAKE + 4, FAKE,
+                 stream=0) == B.TPI_EUNSUPPORTED
+    # all shards of a phase per call: shard count limits, a null entry in the arrays
+    for n in (0, B.TPI_MAX_BATCH_SHARDS + 1):
+        assert _code(B.tpi_shards_layer_prefill, cfg, [_w()] * n, [kv] * n, 0, 4, B.TPI_PHASE_ATTN, FAKE, [FAKE] * n,
+                     [FAKE] * n, stream=0) == B.TPI_EINVAL
+    assert _code(B.tpi_shards_layer_prefill, cfg, [_w()] * 2, [kv] * 2, 0, 4, B.TPI_PHASE_ATTN, FAKE, [FAKE, None],
+                 [FAKE] * 2, stream=0) == B.TPI_EINVAL
+    assert "shard 1" in B.tpi_last_error()
+    assert _code(B.tpi_shards_layer_prefill, cfg, [_w()] * 2, None, 0, 4, B.TPI_PHASE_ATTN, FAKE, [FAKE] * 2,
+                 [FAKE] * 2, stream=0) == B.TPI_EINVAL
 
 
 def test_window_argument_errors_without_a_device():
