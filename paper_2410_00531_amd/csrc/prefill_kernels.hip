@@ -816,9 +816,12 @@ GemmPlan plan_gemm(int M, int N, int K, int max_splits, int share)
     }
     if (M <= 64) p.bm = 64;
     int tiles = cdiv(M, p.bm) * cdiv(N, p.bn);
-    if (tiles < share / 2 && max_splits > 1) {
+    // K is split when the tiles alone leave most of the share idle (one round of workgroups, filled by the
+    // splits), or when they make fewer than three rounds of it (a ragged last round then costs too much).
+    if (max_splits > 1 && (tiles < share / 2 || tiles < 3 * share)) {
         const int ksteps = cdiv(K, 64);
-        int want = std::min(std::min(max_splits, share / tiles), std::max(1, ksteps / 4));
+        const int fill = tiles < share / 2 ? share / tiles : cdiv(3 * share, tiles);
+        int want = std::min(std::min(max_splits, fill), std::max(1, ksteps / (tiles < share / 2 ? 4 : 16)));
         if (want > 1) {
             const int per = cdiv(ksteps, want);
             p.splits = cdiv(ksteps, per);
@@ -840,8 +843,8 @@ PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
     const size_t dq = (size_t)c->n_q_local * c->head_dim, dkv = (size_t)c->n_kv_local * c->head_dim;
     size_t off = 0;
     L.xn = off;  off += align256((size_t)n * c->hidden * 2);
-    const GemmPlan pq = plan_gemm(n, (int)(dq + 2 * dkv), c->hidden, kMaxGemmSplits, 256);
-    size_t qkv = (size_t)pq.splits * n * (dq + 2 * dkv) * 4, gu = (size_t)n * 2 * c->ffn_local * 4;
+    // room for the largest number of K splits a plan can choose, whatever share of the chip the call has
+    size_t qkv = (size_t)kMaxGemmSplits * n * (dq + 2 * dkv) * 4, gu = (size_t)n * 2 * c->ffn_local * 4;
     L.big = off; off += align256(qkv > gu ? qkv : gu);
     L.q = off;   off += align256((size_t)n * dq * 2);
     L.o = off;   off += align256((size_t)n * dq * 2);
