@@ -180,8 +180,23 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int shard = blockIdx.z / g.splits, zs = blockIdx.z - shard * g.splits;
+    // Workgroups are dealt to the eight compute dies in turn (linear index mod 8) and every die has its own L2,
+    // so the tiles are renumbered: each die works through a contiguous run of (z, column tile, row tile) with the
+    // row tile running fastest -- the workgroups that share a B tile, and the neighbours that share A tiles,
+    // meet in one L2 instead of fetching the same rows into several.
+    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    {
+        const unsigned total = gridDim.x * gridDim.y * gridDim.z;
+        if (total % 8 == 0) {
+            const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+            const unsigned item = (lin % 8) * (total / 8) + lin / 8;
+            by = item % gridDim.y;
+            bx = (item / gridDim.y) % gridDim.x;
+            bz = item / (gridDim.y * gridDim.x);
+        }
+    }
+    const int m0 = by * BM, n0 = bx * BN;
+    const int shard = bz / g.splits, zs = bz - shard * g.splits;
     const GemmPtrs P = g.p[shard];
     const int k_begin = zs * g.k_per_split, k_end = min(g.K, k_begin + g.k_per_split);
     float *C = P.C + (size_t)zs * g.c_split;
@@ -202,7 +217,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
         if constexpr (SWI) {
             // tile column -> wave half, pair of 32-column tiles (gate, up), unit within the pair
             const int within = (tid + i * NT) >> 3, wh = within / (BN / 2), t32 = (within % (BN / 2)) >> 5;
-            const int unit = min((int)blockIdx.x * (BN / 2) + wh * (BN / 4) + (t32 >> 1) * 32 + (within & 31), g.n_split - 1);
+            const int unit = min(bx * (BN / 2) + wh * (BN / 4) + (t32 >> 1) * 32 + (within & 31), g.n_split - 1);
             pb[i] = ((t32 & 1) ? P.B1 : P.B0) + (size_t)unit * g.ldb;
         } else {
             int n = min(n0 + ((tid + i * NT) >> 3), g.N - 1);
@@ -216,7 +231,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     // that at any moment the chip's loads are spread over the memory channels instead of all sitting at
     // the same offset of rows a power of two apart.  Only when the K range is whole steps.
     const int span = k_end - k_begin;
-    const int rot = (span % BK == 0 && span >= 32 * BK) ? (blockIdx.x % 16) * BK : 0;
+    const int rot = (span % BK == 0 && span >= 32 * BK) ? (bx % 16) * BK : 0;
 
     uint4 ring[NS][ACH + BCH];
     auto load_tiles = [&](auto J, int k0) {
@@ -335,7 +350,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
         if constexpr (SWI) {
 #pragma unroll
             for (int c = 0; c < NI / 2; ++c) {
-                const int unit = (int)blockIdx.x * (BN / 2) + wn * (BN / 4) + c * 32 + (lane & 31);
+                const int unit = bx * (BN / 2) + wn * (BN / 4) + c * 32 + (lane & 31);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
