@@ -181,18 +181,25 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
     const int wm = wave >> 1, wn = wave & 1;
     // Workgroups are dealt to the eight compute dies in turn (linear index mod 8) and every die has its own L2,
-    // so the tiles are renumbered: each die works through a contiguous run of (z, column tile, row tile) with the
-    // row tile running fastest -- the workgroups that share a B tile, and the neighbours that share A tiles,
-    // meet in one L2 instead of fetching the same rows into several.
+    // so the tiles are renumbered: each die works through a contiguous run of (z, band of kRowBand row tiles,
+    // column tile, row tile of the band) with the row tile running fastest -- the workgroups that share a B
+    // tile, and the neighbours that share A tiles, meet in one L2 instead of fetching the same rows into
+    // several, and with many row tiles (long prompts) a band's A tiles are reused across the column tiles
+    // before the next band starts.
+    constexpr int kRowBand = 8;
     int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
     {
-        const unsigned total = gridDim.x * gridDim.y * gridDim.z;
+        const unsigned gx = gridDim.x, gy = gridDim.y, total = gx * gy * gridDim.z;
         if (total % 8 == 0) {
-            const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+            const unsigned lin = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
             const unsigned item = (lin % 8) * (total / 8) + lin / 8;
-            by = item % gridDim.y;
-            bx = (item / gridDim.y) % gridDim.x;
-            bz = item / (gridDim.y * gridDim.x);
+            bz = item / (gx * gy);
+            unsigned r = item - bz * gx * gy;
+            const unsigned band = min(r / (kRowBand * gx), (gy - 1) / kRowBand);    // the last band may be short
+            const unsigned first = band * kRowBand, rows = min((unsigned)kRowBand, gy - first);
+            r -= band * kRowBand * gx;
+            bx = r / rows;
+            by = first + r % rows;
         }
     }
     const int m0 = by * BM, n0 = bx * BN;
