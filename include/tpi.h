@@ -253,10 +253,10 @@ int tpi_window_release(tpi_window *w, int32_t layer, void *compute_stream);
 int tpi_window_destroy(tpi_window *w);
 
 /*
- * The same window at the paper's granularity (Sec. 3.3: "the memory scheduler
- * asynchronously loads weights for either an attention or FFN block"; window
- * size counted in blocks, Prop. 5) and with block retention (Prop. 6: "retain
- * one FFN block in memory every T FFN blocks").
+ * The same window at the paper's granularity (Sec. 3.3: the unit that is
+ * loaded ahead is one attention block or one FFN block, and the window size
+ * counts blocks, Prop. 5) and with block retention (Prop. 6: one FFN block out
+ * of every T stays in memory for good).
  *
  * A block is any contiguous run of bytes in pinned host memory; in the usual
  * arrangement blocks 2l and 2l+1 are the attention block (attn_norm | w_qkv |
@@ -292,9 +292,9 @@ int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_windo
                              int32_t n_classes, const tpi_window_slots *classes);
 
 /*
- * The paper's own source tier: the weights stay in files ("dynamically loading
- * and unloading model weights", Sec. 3.3; the scheduler "operates on a daemon
- * thread").  Blocks are byte ranges of files; the window owns a loader thread
+ * The paper's own source tier: the weights stay in files and are loaded and
+ * dropped as the layers go by (Sec. 3.3; there the scheduler runs on a
+ * background thread of its own).  Blocks are byte ranges of files; the window owns a loader thread
  * and n_staging pinned staging buffers of the largest block's size; a block of
  * 1 MiB or more is read by n_readers threads (1..64), a contiguous part each.  prefetch
  * only queues the request and returns; the loader reads the block into the
