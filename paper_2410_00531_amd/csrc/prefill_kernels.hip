@@ -163,10 +163,21 @@ struct GemmArgs {
 // written (no fp32 product in memory, no separate elementwise pass).
 constexpr int kSwzShift = 1;
 
-template <int BM, int BN, int NS, int KW, bool SWI = false>
+//
+// DIRECT: the tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane), never
+// through registers: no ds_write, no register ring, and the loads' data does not compete with the fragment
+// reads for the way back into the register file.  Such a load writes the 64 lanes' 16 bytes to consecutive
+// LDS addresses (8 rows of 8 chunks), so the swizzle moves to the global side: the lane at chunk position p
+// of its row fetches K chunk p ^ swizzle(row).  Three LDS stages, each a static array of its own (the
+// compiler then knows that a fragment read of one stage cannot meet a load in flight to another and adds no
+// waits of its own); step t + 2 is requested at the start of step t, and the step ends with an explicit
+// wait for step t + 1's loads of this wave followed by a bare workgroup barrier (a fence would wait for
+// every load in flight).  Needs whole K-steps (K range a multiple of 64) and the eight-wave tiles.
+template <int BM, int BN, int NS, int KW, bool SWI = false, bool DIRECT = false>
 __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
 {
     static_assert(!SWI || BN % 128 == 0, "the fused activation pairs neighbouring 32-column tiles of a wave");
+    static_assert(!DIRECT || (KW == 2 && NS == 3), "the direct loads are written for eight waves and three stages");
     constexpr int BK = 64, NT = 256 * KW;
     constexpr int MI = BM / 64, NI = BN / 64;           // 32x32 tiles per wave along m and n
     constexpr int ACH = BM * (BK / 8) / NT;             // 16-byte chunks per thread, A tile
@@ -176,7 +187,9 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     constexpr int NP = NI > 2 ? 2 : NI;                 // column tiles per pass of the accumulator exchange
     static_assert(NI % NP == 0, "whole passes");
     static_assert(KW == 1 || 8 * NP * 16 * 64 * 4 <= 2 * STAGE * 16, "an exchange pass must fit the LDS stages");
-    extern __shared__ uint4 lds[];                      // 2 * STAGE chunks, sized at launch
+    static_assert(!DIRECT || 8 * 16 * 64 * 4 <= STAGE * 16, "one column tile of an exchange pass per stage");
+    extern __shared__ uint4 lds[];                      // 2 * STAGE chunks, sized at launch (not DIRECT)
+    __shared__ uint4 stage_a[DIRECT ? STAGE : 1], stage_b[DIRECT ? STAGE : 1], stage_c[DIRECT ? STAGE : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
     const int wm = wave >> 1, wn = wave & 1;
@@ -213,7 +226,8 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     // the edge are clamped to the last row (their products are never written), chunks past the end
     // of K are clamped to the last chunk and replaced by zeros after the load.
     const bf16_t *pa[ACH], *pb[BCH];
-    const int kc = (tid & 7) * 8;
+    // K offset of this thread's chunk within a step; DIRECT: the chunk that belongs at LDS position tid & 7
+    const int kc = DIRECT ? ((tid & 7) ^ ((tid >> (3 + kSwzShift)) & 7)) * 8 : (tid & 7) * 8;
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
         int m = min(m0 + ((tid + i * NT) >> 3), g.M - 1);
@@ -240,38 +254,6 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     const int span = k_end - k_begin;
     const int rot = (span % BK == 0 && span >= 32 * BK) ? (bx % 16) * BK : 0;
 
-    uint4 ring[NS][ACH + BCH];
-    auto load_tiles = [&](auto J, int k0) {
-        constexpr int j = decltype(J)::value;
-        int kk = k0 + rot;
-        if (kk >= k_end) kk -= span;
-        const int ko = min(kk + kc, g.K - 8);
-#pragma unroll
-        for (int i = 0; i < ACH; ++i) ring[j][i] = *reinterpret_cast<const uint4 *>(pa[i] + ko);
-#pragma unroll
-        for (int i = 0; i < BCH; ++i) ring[j][ACH + i] = *reinterpret_cast<const uint4 *>(pb[i] + ko);
-    };
-    // k0: the K-step the set was loaded for.  In a step that reaches past k_end the chunks of A at or
-    // past k_end become zeros (B stays as loaded: finite values times zero); this happens here, where
-    // the loaded value is needed anyway (touching it earlier would wait for the load).
-    auto store_tiles = [&](auto J, int stage, int k0) {
-        constexpr int j = decltype(J)::value;
-        uint4 *base = lds + stage * STAGE;
-        if (k0 + BK > k_end) {
-            const unsigned keep = (k0 + kc < k_end) ? 0xffffffffu : 0u;
-#pragma unroll
-            for (int i = 0; i < ACH; ++i) {
-                const uint4 v = ring[j][i];
-                base[st_off + i * NT] = make_uint4(v.x & keep, v.y & keep, v.z & keep, v.w & keep);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < ACH; ++i) base[st_off + i * NT] = ring[j][i];
-        }
-#pragma unroll
-        for (int i = 0; i < BCH; ++i) base[BM * 8 + st_off + i * NT] = ring[j][ACH + i];
-    };
-
     f32x16 acc[MI][NI];
 #pragma unroll
     for (int a = 0; a < MI; ++a)
@@ -283,13 +265,8 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     const int fr = lane & 31, hb = lane >> 5, sw = (fr >> kSwzShift) & 7;
     const int a_row = (wm * (BM / 2) + fr) * 8, b_row = (BM + wn * (BN / 2) + fr) * 8;
 
-    // multiplies the K-step at k0 = step t, with J = (t + 1) % NS: set J - 1 (step t, already in LDS) is
-    // free and takes step t + NS; set J (step t + 1) goes to LDS afterwards
-    auto step = [&](auto J, int k0) {
-        constexpr int j = decltype(J)::value;
-        constexpr int stage = j & 1;
-        load_tiles(std::integral_constant<int, (j + NS - 1) % NS>{}, k0 + NS * BK);
-        const uint4 *base = lds + stage * STAGE;
+    // the fragments of one K-step (this wave's half of it when KW = 2) out of an LDS stage
+    auto multiply = [&](const uint4 *base) {
 #pragma unroll
         for (int s0 = 0; s0 < BK / 16 / KW; ++s0) {
             bf16x8 fa[MI], fb[NI];
@@ -305,51 +282,142 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
                 for (int b = 0; b < NI; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
-        store_tiles(J, stage ^ 1, k0 + BK);   // the other stage was last read before the previous barrier
-        __syncthreads();
     };
 
-    // sets 0 .. NS-1 <- steps 0 .. NS-1, step 0 on to LDS stage 1
-    static_assert(NS % 2 == 0, "LDS stage parity follows the ring index");
-    auto prologue = [&](auto self, auto I) {
-        constexpr int i = decltype(I)::value;
-        if constexpr (i < NS) {
-            load_tiles(I, k_begin + i * BK);
-            self(self, std::integral_constant<int, i + 1>{});
+    if constexpr (DIRECT) {
+        const int nsteps = span / BK;                   // whole steps (the launcher checks)
+        const int w64 = (tid >> 6) * 64;                // this wave's 8 rows of a 64-row slab, in chunks
+        // s_waitcnt immediates: vmcnt in bits 3:0, no wait on the export counter, lgkmcnt 0
+        constexpr int kWaitNext = 0x0070 | (ACH + BCH), kWaitAll = 0x0070;
+        auto request = [&](uint4 *stage, int t) {
+            int kk = k_begin + t * BK + rot;
+            if (kk >= k_end) kk -= span;
+            const int ko = kk + kc;
+#pragma unroll
+            for (int i = 0; i < ACH; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[i] + ko),
+                                                 (__attribute__((address_space(3))) void *)(stage + i * NT + w64), 16, 0, 0);
+#pragma unroll
+            for (int i = 0; i < BCH; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pb[i] + ko),
+                                                 (__attribute__((address_space(3))) void *)(stage + BM * 8 + i * NT + w64), 16, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);          // keep the requests ahead of the step's arithmetic
+        };
+        // Step t out of `cur` while step t + 2 is requested into `nxt` (last read in step t - 1, before that
+        // step's barrier); at the end this wave's loads of step t + 1 have landed, after the barrier everybody's.
+        // The last two steps request the last step once more (cache hits into a free stage) instead of
+        // nothing, so that the count of loads in flight is the same at every wait.
+        auto direct_step = [&](const uint4 *cur, uint4 *nxt, int t) {
+            request(nxt, min(t + 2, nsteps - 1));
+            multiply(cur);
+            __builtin_amdgcn_s_waitcnt(kWaitNext);
+            __builtin_amdgcn_s_barrier();
+        };
+        request(stage_a, 0);
+        request(stage_b, min(1, nsteps - 1));
+        __builtin_amdgcn_s_waitcnt(kWaitNext);
+        __builtin_amdgcn_s_barrier();
+        // whole rounds of three steps (a loop with exits between the steps makes the compiler add a wait for
+        // all loads in flight at its head); every round ends where it began, so the one or two steps left
+        // over start in the first stage again
+        int t = 0;
+        for (; t + 3 <= nsteps; t += 3) {
+            direct_step(stage_a, stage_c, t);
+            direct_step(stage_b, stage_a, t + 1);
+            direct_step(stage_c, stage_b, t + 2);
         }
-    };
-    prologue(prologue, std::integral_constant<int, 0>{});
-    store_tiles(std::integral_constant<int, 0>{}, 1, k_begin);
-    __syncthreads();
-    // always whole rounds of NS steps (no exits inside the round: straight-line code keeps the waits on
-    // the ring exact); steps past k_end multiply zeros
-    auto round = [&](auto self, auto I, int k0) {
-        constexpr int i = decltype(I)::value;
-        if constexpr (i < NS) {
-            step(std::integral_constant<int, (i + 1) % NS>{}, k0 + i * BK);
-            self(self, std::integral_constant<int, i + 1>{}, k0);
-        }
-    };
-    for (int k0 = k_begin; k0 < k_end; k0 += NS * BK) round(round, std::integral_constant<int, 0>{}, k0);
+        if (t < nsteps) direct_step(stage_a, stage_c, t++);
+        if (t < nsteps) direct_step(stage_b, stage_a, t++);
+        __builtin_amdgcn_s_waitcnt(kWaitAll);           // the repeated requests, before the stages are reused
+        __builtin_amdgcn_s_barrier();
+    } else {
+        uint4 ring[NS][ACH + BCH];
+        auto load_tiles = [&](auto J, int k0) {
+            constexpr int j = decltype(J)::value;
+            int kk = k0 + rot;
+            if (kk >= k_end) kk -= span;
+            const int ko = min(kk + kc, g.K - 8);
+    #pragma unroll
+            for (int i = 0; i < ACH; ++i) ring[j][i] = *reinterpret_cast<const uint4 *>(pa[i] + ko);
+    #pragma unroll
+            for (int i = 0; i < BCH; ++i) ring[j][ACH + i] = *reinterpret_cast<const uint4 *>(pb[i] + ko);
+        };
+        // k0: the K-step the set was loaded for.  In a step that reaches past k_end the chunks of A at or
+        // past k_end become zeros (B stays as loaded: finite values times zero); this happens here, where
+        // the loaded value is needed anyway (touching it earlier would wait for the load).
+        auto store_tiles = [&](auto J, int stage, int k0) {
+            constexpr int j = decltype(J)::value;
+            uint4 *base = lds + stage * STAGE;
+            if (k0 + BK > k_end) {
+                const unsigned keep = (k0 + kc < k_end) ? 0xffffffffu : 0u;
+    #pragma unroll
+                for (int i = 0; i < ACH; ++i) {
+                    const uint4 v = ring[j][i];
+                    base[st_off + i * NT] = make_uint4(v.x & keep, v.y & keep, v.z & keep, v.w & keep);
+                }
+            } else {
+    #pragma unroll
+                for (int i = 0; i < ACH; ++i) base[st_off + i * NT] = ring[j][i];
+            }
+    #pragma unroll
+            for (int i = 0; i < BCH; ++i) base[BM * 8 + st_off + i * NT] = ring[j][ACH + i];
+        };
+
+        // multiplies the K-step at k0 = step t, with J = (t + 1) % NS: set J - 1 (step t, already in LDS) is
+        // free and takes step t + NS; set J (step t + 1) goes to LDS afterwards
+        auto step = [&](auto J, int k0) {
+            constexpr int j = decltype(J)::value;
+            constexpr int stage = j & 1;
+            load_tiles(std::integral_constant<int, (j + NS - 1) % NS>{}, k0 + NS * BK);
+            multiply(lds + stage * STAGE);
+            store_tiles(J, stage ^ 1, k0 + BK);   // the other stage was last read before the previous barrier
+            __syncthreads();
+        };
+
+        // sets 0 .. NS-1 <- steps 0 .. NS-1, step 0 on to LDS stage 1
+        static_assert(NS % 2 == 0, "LDS stage parity follows the ring index");
+        auto prologue = [&](auto self, auto I) {
+            constexpr int i = decltype(I)::value;
+            if constexpr (i < NS) {
+                load_tiles(I, k_begin + i * BK);
+                self(self, std::integral_constant<int, i + 1>{});
+            }
+        };
+        prologue(prologue, std::integral_constant<int, 0>{});
+        store_tiles(std::integral_constant<int, 0>{}, 1, k_begin);
+        __syncthreads();
+        // always whole rounds of NS steps (no exits inside the round: straight-line code keeps the waits on
+        // the ring exact); steps past k_end multiply zeros
+        auto round = [&](auto self, auto I, int k0) {
+            constexpr int i = decltype(I)::value;
+            if constexpr (i < NS) {
+                step(std::integral_constant<int, (i + 1) % NS>{}, k0 + i * BK);
+                self(self, std::integral_constant<int, i + 1>{}, k0);
+            }
+        };
+        for (int k0 = k_begin; k0 < k_end; k0 += NS * BK) round(round, std::integral_constant<int, 0>{}, k0);
+
+    }
 
     // KW = 2: the two waves of a pair hold partial sums of the same tiles.  Wave kh hands the other its
     // partial of row tile 1 - kh through LDS (NP column tiles per pass) and finishes row tile kh, so all
     // eight waves share the stores.
+    // column tile b of a pass goes through its own 32 KB: the first two stages when they are separate arrays
+    float *const xch[2] = {reinterpret_cast<float *>(DIRECT ? stage_a : lds),
+                           reinterpret_cast<float *>(DIRECT ? stage_b : lds + 8 * 16 * 64 / 4)};
     auto give = [&](auto A, auto B0) {
         constexpr int a = decltype(A)::value, b0 = decltype(B0)::value;
-        float *xf = reinterpret_cast<float *>(lds);
 #pragma unroll
         for (int b = 0; b < NP; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) xf[(((wave * 2 + a) * NP + b) * 16 + r) * 64 + lane] = acc[a][b0 + b][r];
+            for (int r = 0; r < 16; ++r) xch[b][((wave * 2 + a) * 16 + r) * 64 + lane] = acc[a][b0 + b][r];
     };
     auto take = [&](auto A, auto B0) {
         constexpr int a = decltype(A)::value, b0 = decltype(B0)::value;
-        const float *xf = reinterpret_cast<const float *>(lds);
 #pragma unroll
         for (int b = 0; b < NP; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b0 + b][r] += xf[(((wave * 2 + a) * NP + b) * 16 + r) * 64 + lane];
+            for (int r = 0; r < 16; ++r) acc[a][b0 + b][r] += xch[b][((wave * 2 + a) * 16 + r) * 64 + lane];
     };
     // accumulator register r of lane l is element (8*(r/4) + 4*(l/32) + r%4, l%32) of its 32x32 tile
     auto finish = [&](auto A) {
@@ -876,26 +944,31 @@ PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
 }
 
 // Launches one instantiation with its LDS size; above 64 KB the kernel has to opt in once per device.
-template <int BM, int BN, int NS, int KW, bool SWI>
+template <int BM, int BN, int NS, int KW, bool SWI, bool DIRECT = false>
 hipError_t launch_gemm_kernel(dim3 grid, const GemmArgs &g, hipStream_t st)
 {
-    constexpr size_t lds = (size_t)2 * (BM + BN) * 8 * 16;
-    auto *kern = k_gemm_bf16_nt<BM, BN, NS, KW, SWI>;
-    if constexpr (lds > 65536) {
-        static bool opted[64] = {};
+    // DIRECT: the stages are static arrays of the kernel
+    constexpr size_t lds = DIRECT ? 0 : (size_t)2 * (BM + BN) * 8 * 16;
+    constexpr size_t lds_total = DIRECT ? (size_t)3 * (BM + BN) * 8 * 16 : lds;
+    auto *kern = k_gemm_bf16_nt<BM, BN, NS, KW, SWI, DIRECT>;
+    if constexpr (lds_total > 65536) {
+        static std::atomic<bool> opted[64];
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e != hipSuccess) return e;
         if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-        if (!opted[dev]) {
+        if (!opted[dev].load(std::memory_order_acquire)) {
             e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
-            opted[dev] = true;
+            opted[dev].store(true, std::memory_order_release);
         }
     }
     hipLaunchKernelGGL(kern, grid, dim3(256 * KW), lds, st, g);
     return hipGetLastError();
 }
+
+// The eight-wave tiles load straight into LDS when every K range is whole 64-element steps.
+inline bool direct_ok(const GemmArgs &g) { return g.K % 64 == 0 && g.k_per_split % 64 == 0; }
 
 // max_splits > 1: C must have room for that many partial products of M * ldc floats; the number
 // actually written is returned in *n_parts.
@@ -912,8 +985,12 @@ hipError_t launch_gemm(const GemmPtrs *ptrs, int S, int lda, int n_split, int ld
     for (int s = 0; s < S; ++s) g.p[s] = ptrs[s];
     ProfScope ps(kStagePrefillGemm, st);
     dim3 grid(cdiv(N, p.bn), cdiv(M, p.bm), p.splits * S);
-    if (p.bm == 128 && p.bn == 256) return launch_gemm_kernel<128, 256, 2, 2, false>(grid, g, st);
-    if (p.bm == 128) return launch_gemm_kernel<128, 128, 4, 2, false>(grid, g, st);
+    if (p.bm == 128 && p.bn == 256)
+        return direct_ok(g) ? launch_gemm_kernel<128, 256, 3, 2, false, true>(grid, g, st)
+                            : launch_gemm_kernel<128, 256, 2, 2, false>(grid, g, st);
+    if (p.bm == 128)
+        return direct_ok(g) ? launch_gemm_kernel<128, 128, 3, 2, false, true>(grid, g, st)
+                            : launch_gemm_kernel<128, 128, 4, 2, false>(grid, g, st);
     if (p.bn == 128) return launch_gemm_kernel<64, 128, 4, 1, false>(grid, g, st);
     return launch_gemm_kernel<64, 64, 4, 1, false>(grid, g, st);
 }
@@ -933,11 +1010,14 @@ bool launch_gemm_swiglu(const GemmPtrs *ptrs, int S, int lda, int sl, int ldb, i
     ProfScope ps(kStagePrefillGemm, st);
     if (p.bn == 256) {
         dim3 grid(cdiv(sl, 128), cdiv(M, p.bm), S);
-        *err = launch_gemm_kernel<128, 256, 2, 2, true>(grid, g, st);
+        *err = direct_ok(g) ? launch_gemm_kernel<128, 256, 3, 2, true, true>(grid, g, st)
+                            : launch_gemm_kernel<128, 256, 2, 2, true>(grid, g, st);
         return true;
     }
     dim3 grid(cdiv(sl, 64), cdiv(M, p.bm), S);
-    if (p.bm == 128) *err = launch_gemm_kernel<128, 128, 4, 2, true>(grid, g, st);
+    if (p.bm == 128)
+        *err = direct_ok(g) ? launch_gemm_kernel<128, 128, 3, 2, true, true>(grid, g, st)
+                            : launch_gemm_kernel<128, 128, 4, 2, true>(grid, g, st);
     else *err = launch_gemm_kernel<64, 128, 4, 1, true>(grid, g, st);
     return true;
 }
