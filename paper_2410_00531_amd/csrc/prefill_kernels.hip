@@ -138,7 +138,7 @@ struct GemmPtrs {
     const bf16_t *A;
     const bf16_t *B0, *B1;
     float *C;
-    bf16_t *act;              // SWI kernels only: [M][n_split] output of the fused SwiGLU
+    bf16_t *act;              // SWI kernels only: output of the fused SwiGLU, n_split columns, rows ldc apart
 };
 
 // One launch covers the shards of a batched call: blockIdx.z = shard * splits + K split.
@@ -430,7 +430,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
                 for (int r = 0; r < 16; ++r) {
                     int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     const float gt = acc[a][2 * c][r], up = acc[a][2 * c + 1][r];
-                    if (row < g.M && unit < g.n_split) P.act[(size_t)row * g.n_split + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+                    if (row < g.M && unit < g.n_split) P.act[(size_t)row * g.ldc + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
                 }
             }
         } else {
@@ -998,20 +998,43 @@ hipError_t launch_gemm(const GemmPtrs *ptrs, int S, int lda, int n_split, int ld
 // act[m][j] = bf16(silu(A . gate[j]) * (A . up[j])) in one launch (B0 = gate, B1 = up, act set, C unused).  False
 // (nothing launched) when the plan for this shape uses 64-column tiles: the caller then multiplies and
 // activates separately.
+// When the wide tiles make several rounds of the compute units and the last round is less than 0.6 of one, the
+// hidden units are divided between two launches: wide tiles for as many units as fill whole rounds, 128-column
+// tiles (half the work each) for the rest, so that the chip is not half idle for the length of a wide tile.
 bool launch_gemm_swiglu(const GemmPtrs *ptrs, int S, int lda, int sl, int ldb, int M, int K, hipStream_t st, hipError_t *err)
 {
     const GemmPlan p = plan_gemm(M, 2 * sl, K, 1, std::max(1, current_share() / S));
     *err = hipSuccess;
     if (p.bn < 128) return false;
     GemmArgs g{};
-    g.M = M; g.N = 2 * sl; g.K = K; g.n_split = sl; g.lda = lda; g.ldb = ldb; g.ldc = 0;
+    g.M = M; g.N = 2 * sl; g.K = K; g.n_split = sl; g.lda = lda; g.ldb = ldb; g.ldc = sl;
     g.k_per_split = p.k_per_split; g.splits = 1; g.c_split = 0;
     for (int s = 0; s < S; ++s) g.p[s] = ptrs[s];
     ProfScope ps(kStagePrefillGemm, st);
     if (p.bn == 256) {
-        dim3 grid(cdiv(sl, 128), cdiv(M, p.bm), S);
+        const int cus = std::max(1, current_share()), per_col = cdiv(M, p.bm) * S, cols = cdiv(sl, 128);
+        int wide_cols = cols;
+        const int ragged = (per_col * cols) % cus;
+        if (per_col * cols > cus && ragged != 0 && 10 * ragged < 6 * cus) {
+            for (int c = cols - 1; c >= 1; --c)
+                if ((per_col * c) % cus == 0) { wide_cols = c; break; }
+        }
+        const int wide_units = std::min(sl, wide_cols * 128);
+        g.n_split = wide_units; g.N = 2 * wide_units;
+        dim3 grid(wide_cols, cdiv(M, p.bm), S);
         *err = direct_ok(g) ? launch_gemm_kernel<128, 256, 3, 2, true, true>(grid, g, st)
                             : launch_gemm_kernel<128, 256, 2, 2, true>(grid, g, st);
+        if (*err != hipSuccess || wide_units == sl) return true;
+        // the remaining units: gate and up rows from wide_units on, activation columns from wide_units on
+        g.n_split = sl - wide_units; g.N = 2 * g.n_split;
+        for (int s = 0; s < S; ++s) {
+            g.p[s].B0 += (size_t)wide_units * ldb;
+            g.p[s].B1 += (size_t)wide_units * ldb;
+            g.p[s].act += wide_units;
+        }
+        dim3 rest(cdiv(g.n_split, 64), cdiv(M, p.bm), S);
+        *err = direct_ok(g) ? launch_gemm_kernel<128, 128, 3, 2, true, true>(rest, g, st)
+                            : launch_gemm_kernel<128, 128, 4, 2, true>(rest, g, st);
         return true;
     }
     dim3 grid(cdiv(sl, 64), cdiv(M, p.bm), S);

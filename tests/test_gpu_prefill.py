@@ -354,3 +354,16 @@ def test_prefill_three_layers_two_shards_teacher_forced_and_free_running():
     assert worst_tf <= BF16_TOL
     assert worst_free <= BF16_TOL
 
+
+def test_prefill_gate_up_divided_between_wide_and_narrow_tiles():
+    """When the wide gate|up tiles would end with a nearly empty last round of the compute units, the hidden units
+    are divided between a launch of wide tiles and one of 128-column tiles.  With the hint at its maximum the call
+    counts on 16 compute units, which brings that division to small shapes: 1120 units = 1024 on wide tiles + 96,
+    and, for two shards per call, 616 = 512 + 104 (the last tile ragged in both)."""
+    B.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS)
+    try:
+        _run_prefill_case(320, 2, 1, 64, 1120, 200, 0, 202, seed=5, attn_scale=4.0)
+        test_prefill_batched_call_matches_per_shard_calls_and_oracle(320, 2, 1, 64, 616, 200, 0, 2)
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+
