@@ -367,3 +367,15 @@ def test_prefill_gate_up_divided_between_wide_and_narrow_tiles():
     finally:
         B.tpi_set_prefill_concurrency(1)
 
+
+@pytest.mark.parametrize("steps", [1, 2, 3, 4, 5])
+def test_prefill_direct_to_lds_tiles_with_few_k_steps(steps):
+    """The GEMM variant that loads its tiles straight into LDS runs its K loop in rounds of three steps with the
+    one or two left over after it.  Output projection (K = n_q * 64) and down projection (K = ffn) with 1..5
+    K-steps of 64, on 128x128 tiles (the hint makes the planner keep them at this size)."""
+    B.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS)
+    try:
+        _run_prefill_case(512, steps, 1, 64, 64 * steps, 130, 0, 131, seed=40 + steps, attn_scale=4.0)
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+
