@@ -173,11 +173,13 @@ constexpr int kSwzShift = 1;
 // waits of its own); step t + 2 is requested at the start of step t, and the step ends with an explicit
 // wait for step t + 1's loads of this wave followed by a bare workgroup barrier (a fence would wait for
 // every load in flight).  Needs whole K-steps (K range a multiple of 64) and the eight-wave tiles.
+// NS = 2 is the same with two stages (step t + 1 requested at the start of step t): half the LDS, so that two
+// workgroups fit a compute unit.
 template <int BM, int BN, int NS, int KW, bool SWI = false, bool DIRECT = false>
 __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
 {
     static_assert(!SWI || BN % 128 == 0, "the fused activation pairs neighbouring 32-column tiles of a wave");
-    static_assert(!DIRECT || (KW == 2 && NS == 3), "the direct loads are written for eight waves and three stages");
+    static_assert(!DIRECT || (KW == 2 && (NS == 3 || NS == 2)), "the direct loads are written for eight waves and two or three stages");
     constexpr int BK = 64, NT = 256 * KW;
     constexpr int MI = BM / 64, NI = BN / 64;           // 32x32 tiles per wave along m and n
     constexpr int ACH = BM * (BK / 8) / NT;             // 16-byte chunks per thread, A tile
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     static_assert(KW == 1 || 8 * NP * 16 * 64 * 4 <= 2 * STAGE * 16, "an exchange pass must fit the LDS stages");
     static_assert(!DIRECT || 8 * 16 * 64 * 4 <= STAGE * 16, "one column tile of an exchange pass per stage");
     extern __shared__ uint4 lds[];                      // 2 * STAGE chunks, sized at launch (not DIRECT)
-    __shared__ uint4 stage_a[DIRECT ? STAGE : 1], stage_b[DIRECT ? STAGE : 1], stage_c[DIRECT ? STAGE : 1];
+    __shared__ uint4 stage_a[DIRECT ? STAGE : 1], stage_b[DIRECT ? STAGE : 1], stage_c[DIRECT && NS == 3 ? STAGE : 1];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
     const int wm = wave >> 1, wn = wave & 1;
@@ -313,6 +315,25 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
             __builtin_amdgcn_s_waitcnt(kWaitNext);
             __builtin_amdgcn_s_barrier();
         };
+        if constexpr (NS == 2) {
+            // two stages (half the LDS: two workgroups per compute unit): step t + 1 is requested at the start of
+            // step t into the stage that step t - 1 was read from, and must have landed at the end of step t
+            auto step2 = [&](const uint4 *cur, uint4 *nxt, int t) {
+                request(nxt, min(t + 1, nsteps - 1));
+                multiply(cur);
+                __builtin_amdgcn_s_waitcnt(kWaitAll);
+                __builtin_amdgcn_s_barrier();
+            };
+            request(stage_a, 0);
+            __builtin_amdgcn_s_waitcnt(kWaitAll);
+            __builtin_amdgcn_s_barrier();
+            int t = 0;
+            for (; t + 2 <= nsteps; t += 2) {
+                step2(stage_a, stage_b, t);
+                step2(stage_b, stage_a, t + 1);
+            }
+            if (t < nsteps) step2(stage_a, stage_b, t++);
+        } else {
         request(stage_a, 0);
         request(stage_b, min(1, nsteps - 1));
         __builtin_amdgcn_s_waitcnt(kWaitNext);
@@ -330,6 +351,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
         if (t < nsteps) direct_step(stage_b, stage_a, t++);
         __builtin_amdgcn_s_waitcnt(kWaitAll);           // the repeated requests, before the stages are reused
         __builtin_amdgcn_s_barrier();
+        }
     } else {
         uint4 ring[NS][ACH + BCH];
         auto load_tiles = [&](auto J, int k0) {
@@ -949,7 +971,7 @@ hipError_t launch_gemm_kernel(dim3 grid, const GemmArgs &g, hipStream_t st)
 {
     // DIRECT: the stages are static arrays of the kernel
     constexpr size_t lds = DIRECT ? 0 : (size_t)2 * (BM + BN) * 8 * 16;
-    constexpr size_t lds_total = DIRECT ? (size_t)3 * (BM + BN) * 8 * 16 : lds;
+    constexpr size_t lds_total = DIRECT ? (size_t)NS * (BM + BN) * 8 * 16 : lds;
     auto *kern = k_gemm_bf16_nt<BM, BN, NS, KW, SWI, DIRECT>;
     if constexpr (lds_total > 65536) {
         static std::atomic<bool> opted[64];
@@ -988,9 +1010,15 @@ hipError_t launch_gemm(const GemmPtrs *ptrs, int S, int lda, int n_split, int ld
     if (p.bm == 128 && p.bn == 256)
         return direct_ok(g) ? launch_gemm_kernel<128, 256, 3, 2, false, true>(grid, g, st)
                             : launch_gemm_kernel<128, 256, 2, 2, false>(grid, g, st);
-    if (p.bm == 128)
-        return direct_ok(g) ? launch_gemm_kernel<128, 128, 3, 2, false, true>(grid, g, st)
-                            : launch_gemm_kernel<128, 128, 4, 2, false>(grid, g, st);
+    if (p.bm == 128) {
+        if (!direct_ok(g)) return launch_gemm_kernel<128, 128, 4, 2, false>(grid, g, st);
+        // With at least two workgroups per compute unit the two-stage variant (64 KB of LDS, two workgroups
+        // resident) lets one workgroup's start and end overlap the other's K loop: QKV of 8 shards 126 -> 106 us.
+        // With one workgroup per compute unit the deeper pipeline of the three-stage variant is what counts.
+        if ((int)(grid.x * grid.y * grid.z) >= 2 * std::max(1, current_share()))
+            return launch_gemm_kernel<128, 128, 2, 2, false, true>(grid, g, st);
+        return launch_gemm_kernel<128, 128, 3, 2, false, true>(grid, g, st);
+    }
     if (p.bn == 128) return launch_gemm_kernel<64, 128, 4, 1, false>(grid, g, st);
     return launch_gemm_kernel<64, 64, 4, 1, false>(grid, g, st);
 }

@@ -379,3 +379,16 @@ def test_prefill_direct_to_lds_tiles_with_few_k_steps(steps):
     finally:
         B.tpi_set_prefill_concurrency(1)
 
+
+@pytest.mark.parametrize("h", [512, 576])
+def test_prefill_two_stage_direct_tiles(h):
+    """A 128x128-tile GEMM with at least two workgroups per compute unit takes the two-stage variant of the
+    direct-to-LDS loop (two workgroups resident per compute unit).  QKV with 2048 output rows on 130 tokens is
+    32 tiles; under the maximum hint the call counts on 16 compute units.  8 and 9 K-steps: an even count and
+    one left over."""
+    B.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS)
+    try:
+        _run_prefill_case(h, 24, 4, 64, 256, 130, 0, 131, seed=h, attn_scale=4.0)
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+
