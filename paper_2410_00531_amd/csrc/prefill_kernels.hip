@@ -1013,7 +1013,7 @@ hipError_t launch_gemm(const GemmPtrs *ptrs, int S, int lda, int n_split, int ld
     if (p.bm == 128) {
         if (!direct_ok(g)) return launch_gemm_kernel<128, 128, 4, 2, false>(grid, g, st);
         // With at least two workgroups per compute unit the two-stage variant (64 KB of LDS, two workgroups
-        // resident) lets one workgroup's start and end overlap the other's K loop: QKV of 8 shards 126 -> 106 us.
+        // resident) lets one workgroup's start and end overlap the other's K loop: QKV of 8 shards 126 -> 119 us.
         // With one workgroup per compute unit the deeper pipeline of the three-stage variant is what counts.
         if ((int)(grid.x * grid.y * grid.z) >= 2 * std::max(1, current_share()))
             return launch_gemm_kernel<128, 128, 2, 2, false, true>(grid, g, st);
