@@ -888,6 +888,198 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// The same attention with the key and value tiles shared by 128 rows (head_dim 64 or 128)
+// ---------------------------------------------------------------------------
+// A workgroup owns 128 consecutive rows of one KV head, 32 per wave; every wave walks ALL key tiles its rows can
+// see, against tiles that the workgroup brings into LDS once (global_load_lds, three stages, as in the GEMM):
+// a quarter of the traffic per row of the kernel above, and no merge of the waves at the end.  Scores
+// transposed as above, K fragments read from LDS rows swizzled against bank conflicts, and the V^T fragments
+// come out of the row-major V tile through the transposing LDS read (ds_read_b64_tr_b16: in a group of 16
+// lanes, lane 4i + j receives element j of the 8-byte pieces that lanes i, i + 4, i + 8, i + 12 point at --
+// with lane s pointing at key s / 4, elements 4 (s % 4) .. + 3, lane l ends up with 4 consecutive keys of
+// element l).  Workgroups with the longest rows come first in the grid.
+typedef short tr16x4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void k_prefill_attn_shared(AttnArgs a)
+{
+    static_assert(D == 64 || D == 128, "tile loads are laid out for these head sizes");
+    constexpr int ET = D / 32, KS = D / 16, TK = 32;
+    constexpr int CPR = D / 8;                                   // 16-byte chunks per row
+    constexpr int TILE = TK * CPR;                               // chunks per K or V tile
+    constexpr int NLD = TILE / 64 / 4;                           // loads per wave per tile (K, and again V)
+    constexpr int kWaitNext = 0x0070 | (2 * NLD), kWaitAll = 0x0070;
+    __shared__ uint4 k_a[TILE], k_b[TILE], k_c[TILE], v_a[TILE], v_b[TILE], v_c[TILE];
+
+    const bf16_t *__restrict__ q = a.q[blockIdx.z];
+    bf16_t *__restrict__ o = a.o[blockIdx.z];
+    const int n = a.n, nq = a.nq, nkv = a.nkv, max_seq = a.max_seq, pos0 = a.pos0;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, hb = lane >> 5;
+    const int G = nq / nkv, gk = blockIdx.y;
+    const int n_rows = n * G;
+    const int blk = gridDim.x - 1 - blockIdx.x;                  // longest rows first
+    const int row = blk * 128 + wave * 32 + col;
+    const bool row_ok = row < n_rows;
+    const int tok = row_ok ? row / G : n - 1, head = gk * G + (row_ok ? row % G : 0);
+    const int my_last = pos0 + tok;
+    const int wave_last_key = pos0 + min(n - 1, (blk * 128 + wave * 32 + 31) / G);
+    const int wg_last_key = pos0 + min(n - 1, (blk * 128 + 127) / G);
+    const int ntiles = wg_last_key / TK + 1;
+    const float scale = 1.0f / sqrtf((float)D);
+    const bf16_t *Kg = a.Kc[blockIdx.z] + (size_t)gk * max_seq * D;
+    const bf16_t *Vg = a.Vc[blockIdx.z] + (size_t)gk * max_seq * D;
+
+    bf16x8 qf[KS];
+    {
+        const bf16_t *qp = q + ((size_t)tok * nq + head) * D + hb * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+    }
+    f32x16 oacc[ET];
+#pragma unroll
+    for (int et = 0; et < ET; ++et)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[et][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    // This lane's pieces of a tile: load i of the wave covers chunks (wave * NLD + i) * 64 .. + 63, i.e. tile row
+    // c / CPR at chunk position c % CPR, which holds the row's chunk (position ^ swizzle(row)).
+    // K rows: swizzle so that the 16 keys a fragment read serves at a time hit 16 different chunk columns;
+    // V rows: so that the 4 keys of a transposing read hit different pairs of chunks.
+    constexpr int RP = 128 / D;                                  // rows per 256 bytes of LDS
+    auto swz_k = [](int r) { return (r / RP) % CPR; };
+    auto swz_v = [](int r) { return 2 * (r & 3); };
+    int ld_row[NLD], ld_kc[NLD], ld_vc[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int c = (wave * NLD + i) * 64 + lane;
+        ld_row[i] = c / CPR;
+        ld_kc[i] = ((c % CPR) ^ swz_k(ld_row[i])) * 8;
+        ld_vc[i] = ((c % CPR) ^ swz_v(ld_row[i])) * 8;
+    }
+    auto request = [&](uint4 *ks, uint4 *vs, int t) {
+        const int k0 = t * TK;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const size_t key = (size_t)min(k0 + ld_row[i], wg_last_key);     // always in bounds; masked below
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Kg + key * D + ld_kc[i]),
+                                             (__attribute__((address_space(3))) void *)(ks + (wave * NLD + i) * 64), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Vg + key * D + ld_vc[i]),
+                                             (__attribute__((address_space(3))) void *)(vs + (wave * NLD + i) * 64), 16, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // fragment addresses (bytes within a tile)
+    const int k_off = col * (D * 2);                             // K fragment: row = key col, chunk 2 ks + hb
+    const int k_sw = swz_k(col);
+    // V^T fragment for output tile et, MFMA step s2, half hf: keys 16 s2 + 8 hf + 4 hb .. + 3 of elements
+    // 32 et + 16 ((lane >> 4) & 1) + (lane & 15); this lane points at key .. + (lane & 15) / 4, elements 4 (lane & 3)
+    const int v_key = 4 * hb + ((lane & 15) >> 2);
+    const int v_el = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
+    auto compute = [&](const uint4 *ks, const uint4 *vs, int t) {
+        const int k0 = t * TK;
+        if (k0 > wave_last_key) return;                          // none of this wave's rows sees the tile
+        const unsigned char *kb = reinterpret_cast<const unsigned char *>(ks);
+        const unsigned char *vb = reinterpret_cast<const unsigned char *>(vs);
+        f32x16 sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + k_off + (((2 * s + hb) ^ k_sw) << 4));
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc, 0, 0, 0);
+        }
+        // register r of this lane: key k0 + 8*(r/4) + 4*hb + r%4, row = this lane's column
+        float mt = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            int key = k0 + 8 * (r >> 2) + 4 * hb + (r & 3);
+            float sv = (key <= my_last) ? sacc[r] * scale : -INFINITY;
+            sacc[r] = sv;
+            mt = fmaxf(mt, sv);
+        }
+        mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+        const float m_new = fmaxf(m_run, mt);
+        float ls = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float p = (sacc[r] == -INFINITY) ? 0.f : __expf(sacc[r] - m_new);
+            sacc[r] = p;
+            ls += p;
+        }
+        ls += __shfl_xor(ls, 32, 64);
+        const float alpha = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+        l_run = l_run * alpha + ls;
+        m_run = m_new;
+        if (__any(alpha != 1.0f)) {                             // the maxima settle after the first tiles
+#pragma unroll
+            for (int et = 0; et < ET; ++et)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[et][r] *= alpha;
+        }
+        bf16x8 pf[2];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            union { bf16x8 v; bf16_t u[8]; } cvt;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) cvt.u[i] = f32_to_bf16(sacc[8 * s2 + i]);
+            pf[s2] = cvt.v;
+        }
+#pragma unroll
+        for (int et = 0; et < ET; ++et) {
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                union { bf16x8 v; tr16x4 h[2]; } vf;
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    const int key = 16 * s2 + 8 * hf + v_key, el = 32 * et + v_el;
+                    const int off = key * (D * 2) + ((((el >> 3) ^ swz_v(key)) << 4) | ((el & 7) << 1));
+                    vf.h[hf] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) tr16x4 *)(vb + off));
+                }
+                oacc[et] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[s2], oacc[et], 0, 0, 0);
+            }
+        }
+    };
+    auto step = [&](const uint4 *ks, const uint4 *vs, uint4 *kn, uint4 *vn, int t) {
+        request(kn, vn, min(t + 2, ntiles - 1));
+        compute(ks, vs, t);
+        __builtin_amdgcn_s_waitcnt(kWaitNext);
+        __builtin_amdgcn_s_barrier();
+    };
+    request(k_a, v_a, 0);
+    request(k_b, v_b, min(1, ntiles - 1));
+    __builtin_amdgcn_s_waitcnt(kWaitNext);
+    __builtin_amdgcn_s_barrier();
+    int t = 0;
+    for (; t + 3 <= ntiles; t += 3) {
+        step(k_a, v_a, k_c, v_c, t);
+        step(k_b, v_b, k_a, v_a, t + 1);
+        step(k_c, v_c, k_b, v_b, t + 2);
+    }
+    if (t < ntiles) step(k_a, v_a, k_c, v_c, t++);
+    if (t < ntiles) step(k_b, v_b, k_a, v_a, t++);
+    __builtin_amdgcn_s_waitcnt(kWaitAll);
+
+    if (row_ok) {
+        const float inv = 1.0f / l_run;
+        bf16_t *op = o + ((size_t)tok * nq + head) * D;
+#pragma unroll
+        for (int et = 0; et < ET; ++et)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                // registers 4*r4 .. 4*r4+3: elements e = 32*et + 8*r4 + 4*hb + 0..3
+                union { uint2 v; bf16_t u[4]; } pk;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pk.u[i] = f32_to_bf16(oacc[et][4 * r4 + i] * inv);
+                *reinterpret_cast<uint2 *>(op + 32 * et + 8 * r4 + 4 * hb) = pk.v;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
 namespace {
@@ -1146,6 +1338,16 @@ int prefill_launch(const tpi_shard_cfg *c, int S, const tpi_layer_weights *w, co
             aa.n = n; aa.nq = nq; aa.nkv = nkv; aa.max_seq = c->max_seq; aa.pos0 = pos0;
             for (int s = 0; s < S; ++s) { aa.q[s] = qb[s]; aa.Kc[s] = (const bf16_t *)kv[s].k; aa.Vc[s] = (const bf16_t *)kv[s].v; aa.o[s] = ob[s]; }
             dim3 grid((n * G + 31) / 32, nkv, S);
+            // With at least one 128-row workgroup per compute unit the kernel that shares its key and value
+            // tiles among 128 rows is ahead (one shard, 16 layers: 16384-token prompt 130 -> 96 ms, 4096 tokens
+            // 23.4 -> 23.0 ms); below that the 32-row kernel, whose waves split the keys, has the shorter
+            // critical path (2048 tokens: 11.85 against 12.2 ms; 512 tokens, one shard: 16 against 34 us).
+            const long wg128 = (long)((n * G + 127) / 128) * nkv * S;
+            if ((d == 64 || d == 128) && wg128 >= std::max(1, current_share())) {
+                dim3 g2((n * G + 127) / 128, nkv, S);
+                if (d == 64) hipLaunchKernelGGL((k_prefill_attn_shared<64>), g2, dim3(256), 0, st, aa);
+                else hipLaunchKernelGGL((k_prefill_attn_shared<128>), g2, dim3(256), 0, st, aa);
+            } else
             switch (d) {
             case 32: hipLaunchKernelGGL((k_prefill_attn_mfma<32>), grid, dim3(256), 0, st, aa); break;
             case 64: hipLaunchKernelGGL((k_prefill_attn_mfma<64>), grid, dim3(256), 0, st, aa); break;

@@ -392,3 +392,20 @@ def test_prefill_two_stage_direct_tiles(h):
     finally:
         B.tpi_set_prefill_concurrency(1)
 
+
+@pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0", [
+    (256, 16, 4, 64, 64, 300, 5),      # 4 heads per KV head, non-empty cache, 1200 rows per KV head: a ragged last block
+    (512, 8, 1, 128, 64, 530, 0),      # head_dim 128, 8 heads on one KV head, 17 key tiles (rounds of three and two left over)
+    (256, 4, 4, 64, 64, 1030, 0),      # one head per KV head
+    (256, 8, 2, 64, 64, 260, 33),      # keys before the prompt: every row sees at least two tiles
+])
+def test_prefill_attention_with_tiles_shared_by_128_rows(h, nq, nkv, d, sl, n, pos0):
+    """Prompts with at least one 128-row workgroup per compute unit take the attention kernel that brings each
+    key / value tile into LDS once per 128 rows and reads V through the transposing LDS load.  The maximum hint
+    (16 compute units to count on) brings that choice to these sizes."""
+    B.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS)
+    try:
+        _run_prefill_case(h, nq, nkv, d, sl, n, pos0, pos0 + n + 1, seed=h + n + d, attn_scale=4.0)
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+
