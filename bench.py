@@ -65,7 +65,7 @@ def parse():
                     help="T of the retention variant: the FFN block of every T-th layer stays resident")
     ap.add_argument("--no-window-prefill", action="store_true",
                     help="skip the windowed long-prompt prefill (the point where the copies can hide)")
-    ap.add_argument("--window-prefill-tokens", type=int, default=16384)
+    ap.add_argument("--window-prefill-tokens", type=int, default=24576)
     ap.add_argument("--window-prefill-layers", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
