@@ -545,7 +545,7 @@ def window_prefill_leg(args, m, seed):
 
 
 def prefill_leg(args, m, L, N, seed):
-    """BASELINE config 5: prompt of --prefill-tokens tokens through the whole stack, all N shards emulated,
+    """The prefill workload (70B-shaped 8-way shard, 512 tokens by default): prompt of --prefill-tokens tokens through the whole stack, all N shards emulated,
     bf16 weights and activations, fp32 partials star-reduced per layer (the reduce also emits the bf16 copy
     that feeds the next phase)."""
     import torch

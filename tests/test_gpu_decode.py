@@ -20,7 +20,7 @@ def _cfg_of(m: configs.ModelShape, max_seq):
 
 
 def test_tiny_config_two_layers_two_shards():
-    """BASELINE config 1: teacher-forced per-shard parity and the free-running stack."""
+    """The tiny 2-layer, 2-shard workload: teacher-forced per-shard parity and the free-running stack."""
     m = configs.TINY
     pos, max_seq = 16, 24
     weights, caches, h0 = synth.stack_from_shape(m, seed=0, n_cached=pos, max_seq=max_seq)
@@ -252,7 +252,7 @@ def test_token_captured_in_a_graph_replays_to_the_eager_result():
 
 
 def test_8b_shaped_layer_all_shards():
-    """BASELINE config 2 shape: one layer, N = 4, KV length 512."""
+    """The 8B-shaped 4-way shard: one layer, N = 4, KV length 512."""
     m = configs.LLAMA31_8B_TP4
     pos, max_seq = 512, 520
     weights, caches, h0 = synth.stack_from_shape(m, seed=1, n_cached=pos, max_seq=max_seq, n_layers=1)
@@ -271,7 +271,7 @@ def test_8b_shaped_layer_all_shards():
 
 
 def test_70b_shaped_layer_all_shards():
-    """BASELINE config 3 shape and launch configuration (8 shards batched, KV
+    """The 70B-shaped 8-way shard in the launch configuration the benchmark times (8 shards batched, KV
     length 1024): weights drawn on the device, the oracle gets the same bytes."""
     m = configs.LLAMA2_70B_TP8
     pos, max_seq = 1024, 1032
@@ -315,7 +315,7 @@ def test_70b_shaped_layer_all_shards():
 
 
 def test_70b_shaped_stack_two_tokens_free_running_and_teacher_forced():
-    """Six layers of the BASELINE config 3 stack (8 shards batched per launch, KV length 1024), two
+    """Six layers of the 70B-shaped 8-way stack (8 shards batched per launch, KV length 1024), two
     tokens in a row.  Free-running: the device feeds itself and is compared with the oracle feeding
     itself, layer by layer.  Teacher-forced: every device layer is also run from the oracle's input of
     that layer, so a drift of the free-running comparison cannot hide behind accumulated error."""

@@ -130,7 +130,7 @@ def test_prefill_8b_shaped_layer_one_shard():
 
 
 def test_prefill_70b_shaped_layer_one_shard_512_tokens():
-    """BASELINE config 5 shape: 512 prompt tokens, empty cache, one shard of one layer."""
+    """The benchmark's prefill shape (70B-shaped 8-way shard): 512 prompt tokens, empty cache, one shard of one layer."""
     m = configs.LLAMA2_70B_TP8
     _run_prefill_case(m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local, 512, 0, 512, seed=70)
 
