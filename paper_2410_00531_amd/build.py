@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libtpi.so")
 SOURCES = ["tpi_api.hip", "decode_kernels.hip", "decode_persistent.hip", "star_reduce.hip", "prefill_kernels.hip", "window.hip", "prof.hip", "token_ends.hip"]
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     "-fno-gpu-rdc", "-ffp-contract=on",
     # scalar fp32 code only: never let the compiler form packed fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -19,9 +19,7 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_lib(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -33,6 +31,20 @@ def build_lib(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and err.strip():
         print(err)
+
+
+def build_lib(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    """Compiles every source (in parallel, objects under _build/) and links libtpi.so."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[hipcc, *HIPCC_FLAGS, *extra_flags, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    jobs = max(1, min(len(cmds), int(os.environ.get("MAX_JOBS", "0")) or (os.cpu_count() or 1), 16))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc, "--offload-arch=gfx950", "-fno-gpu-rdc", "-shared", "-fPIC", "-o", out, *objs], verbose)
     return out
 
 
