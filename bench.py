@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--window-layers", type=int, default=4)
     ap.add_argument("--window-steps", type=int, default=3)
     ap.add_argument("--no-fused", action="store_true", help="skip the reduce-folded-into-phase leg")
+    ap.add_argument("--separate-reduce", action="store_true",
+                    help="time the all-shards step with separate star-reduce launches (default: folded into the "
+                         "row-parallel stage, bitwise the same result)")
     ap.add_argument("--persistent", dest="no_persistent", action="store_false", default=True,
                     help="also time the whole-token persistent kernel (switched off in the library for now)")
     ap.add_argument("--no-prefill", action="store_true", help="skip the bf16 prefill leg")
@@ -828,14 +831,23 @@ def main():
             raise RuntimeError(B.tpi_last_error())
 
     last_out = [h0]
+    fold_all = not args.separate_reduce
 
-    def token(pos, all_shards=True, fused=False):
+    def token(pos, all_shards=True, fused=None):
         """One token through the stack; returns the output hidden state tensor.  All shards: batched
         phase launches + star reduce kernels.  One shard: one device's view; the 8-way reduce runs over
         its own partial and the 7 peers' partial buffers, either as the separate star-reduce launch or
         (fused) folded into the phase's last stage."""
         src, dst = h0, h_a
-        if all_shards:
+        if all_shards and (fold_all if fused is None else fused):
+            # every phase with its star reduce folded into the row-parallel stage: 2 calls, 5 launches per layer
+            for l in range(L):
+                check(lib.tpi_shards_layer_decode_reduce(cfg_p, N, W_all[l], KV_all[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
+                                                         h_attn.data_ptr(), WS_all, stream))
+                check(lib.tpi_shards_layer_decode_reduce(cfg_p, N, W_all[l], None, pos, B.TPI_PHASE_FFN, h_attn.data_ptr(),
+                                                         dst.data_ptr(), WS_all, stream))
+                src, dst = dst, (h_b if dst is h_a else h_a)
+        elif all_shards:
             for l in range(L):
                 check(lib.tpi_shards_layer_decode(cfg_p, N, W_all[l], KV_all[l], pos, B.TPI_PHASE_ATTN, src.data_ptr(),
                                                   P_all, WS_all, stream))
@@ -903,8 +915,22 @@ def main():
     gu_n = gu1_n = 0
     if args.mode in ("both", "all"):
         ms_all, med_all, gu_ms, gu_n = leg(True)
-    else:
-        token(pos, True); pos += 1                 # fills the peer partials once
+    reduce_cmp = None
+    if args.mode in ("both", "all") and fold_all:
+        # the same step with the star reduces as launches of their own (the partial vectors go through memory):
+        # same bits, 7 launches per layer instead of 5
+        out_f = token(pos, True, True).clone()
+        out_s = token(pos, True, False).clone()      # same position: rewrites the same cache slot with the same values
+        pos += 1
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(K):
+            token(pos + i, True, False)
+        torch.cuda.synchronize()
+        reduce_cmp = {"ms_per_token_separate_reduce_launches": round((time.perf_counter() - t) * 1e3 / K, 4),
+                      "folded_equals_separate_bitwise": bool(torch.equal(out_f, out_s))}
+        pos += K
+    token(pos, True, False); pos += 1              # fills the peer partial buffers the one-shard legs read
     if args.mode in ("both", "one"):
         # one device's shard (peer partials stay as the last full step left them)
         ms_one, med_one, gu1_ms, gu1_n = leg(False)
@@ -991,6 +1017,10 @@ def main():
         "algorithmic_gb_per_token": round(bytes_all / 1e9, 3),
         "hbm_gbps": round(gbps_all, 1),
         "hbm_frac_of_peak": round(gbps_all / HBM_PEAK_GBPS, 4),
+        # the timed step calls tpi_shards_layer_decode_reduce (star reduce folded into the row-parallel stage)
+        # unless --separate-reduce; the other arrangement and the bitwise comparison of the two:
+        "star_reduce": ("separate launches" if not fold_all else "folded into the row-parallel stage") if args.mode != "one" else None,
+        "star_reduce_arrangements": reduce_cmp,
         "one_shard": None if args.mode == "all" else {"ms_per_token": round(ms_one, 4), "ms_per_token_median_events": round(med_one, 4),
                       "tokens_per_s": round(1e3 / ms_one, 2),
                       "algorithmic_gb_per_token": round(bytes_one / 1e9, 3), "hbm_gbps": round(gbps_one, 1),

@@ -151,6 +151,23 @@ int tpi_shards_layer_decode(const tpi_shard_cfg *cfg, int32_t n_shards,
                             void *stream);
 
 /*
+ * The batched phase with the star reduce and the shortcut folded in (the whole
+ * step between two layer inputs of Alg. 1: every device's block, then
+ * all_reduce + shortcut): all n_shards ranks' partials are formed by this
+ * call and
+ *   out[i] = (((p0[i] + p1[i]) + ...) + p_{n-1}[i]) + h_in[i]
+ * bit for bit what tpi_shards_layer_decode followed by
+ * tpi_star_reduce(residual = h_in) yields; the partial vectors are not written
+ * to memory (the last, row-parallel stage walks the ranks in order for its
+ * rows of the output).  out [h] fp32, must not alias h_in.  Arguments and
+ * errors otherwise as for tpi_shards_layer_decode.
+ */
+int tpi_shards_layer_decode_reduce(const tpi_shard_cfg *cfg, int32_t n_shards,
+                                   const tpi_layer_weights *host_w, const tpi_kv_layer *host_kv,
+                                   int32_t pos, int phase, const float *h_in, float *out,
+                                   void *const *host_workspace, void *stream);
+
+/*
  * Prefill: the same two phases for n_tokens consecutive prompt tokens at
  * positions pos0 .. pos0+n_tokens-1 with causal attention (token i sees slots
  * 0..pos0+i), filling cache slots pos0..pos0+n_tokens-1 and no others.

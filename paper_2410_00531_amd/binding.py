@@ -24,7 +24,7 @@ TPI_MAX_BATCH_SHARDS = 16
 
 EXPORTED = (
     "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode", "tpi_set_prefill_concurrency", "tpi_shards_layer_prefill",
-    "tpi_shard_layer_decode_reduce",
+    "tpi_shard_layer_decode_reduce", "tpi_shards_layer_decode_reduce",
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create",
     "tpi_window_create_blocks", "tpi_window_create_files", "tpi_window_read_stats", "tpi_window_prefetch",
     "tpi_embed_token", "tpi_lm_head", "tpi_next_token",
@@ -102,6 +102,11 @@ def lib() -> C.CDLL:
                                               C.POINTER(tpi_layer_weights), C.POINTER(tpi_kv_layer),
                                               C.c_int32, C.c_int, C.c_void_p, C.POINTER(C.c_void_p),
                                               C.POINTER(C.c_void_p), C.c_void_p]
+        l.tpi_shards_layer_decode_reduce.restype = C.c_int
+        l.tpi_shards_layer_decode_reduce.argtypes = [C.POINTER(tpi_shard_cfg), C.c_int32,
+                                                     C.POINTER(tpi_layer_weights), C.POINTER(tpi_kv_layer),
+                                                     C.c_int32, C.c_int, C.c_void_p, C.c_void_p,
+                                                     C.POINTER(C.c_void_p), C.c_void_p]
         l.tpi_shard_layer_prefill.restype = C.c_int
         l.tpi_shard_layer_prefill.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
                                               C.POINTER(tpi_kv_layer), C.c_int32, C.c_int32, C.c_int,
@@ -255,6 +260,20 @@ def tpi_shards_layer_decode(cfg, weights: Sequence[tpi_layer_weights],
     wsarr = workspaces if isinstance(workspaces, C.Array) else (C.c_void_p * n)(*[_ptr(p) for p in workspaces])
     _check(lib().tpi_shards_layer_decode(C.byref(cfg), n, warr, karr, pos, phase, _ptr(h_in), parr,
                                          wsarr, _stream(stream)))
+
+
+def tpi_shards_layer_decode_reduce(cfg, weights: Sequence[tpi_layer_weights],
+                                   kvs: Optional[Sequence[tpi_kv_layer]], pos: int, phase: int, h_in, out,
+                                   workspaces, stream=None) -> None:
+    n = len(weights)
+    warr = weights if isinstance(weights, C.Array) else (tpi_layer_weights * n)(*weights)
+    if kvs is None:
+        karr = None
+    else:
+        karr = kvs if isinstance(kvs, C.Array) else (tpi_kv_layer * n)(*kvs)
+    wsarr = workspaces if isinstance(workspaces, C.Array) else (C.c_void_p * n)(*[_ptr(p) for p in workspaces])
+    _check(lib().tpi_shards_layer_decode_reduce(C.byref(cfg), n, warr, karr, pos, phase, _ptr(h_in), _ptr(out),
+                                                wsarr, _stream(stream)))
 
 
 def tpi_shards_layer_prefill(cfg, weights: Sequence[tpi_layer_weights], kvs: Optional[Sequence[tpi_kv_layer]],

@@ -41,6 +41,7 @@ struct DecodeDims {
 // is in registers, the peers' partials are in memory).  out[i] = sum in rank order, then + residual.
 struct FusedReduce {
     int n = 0, rank = 0;                  // n == 0: no folding, the stage stores its partial
+    int all = 0;                          // batched call: all n ranks' partials are formed by this launch (no peers)
     const float *residual = nullptr;
     float *out = nullptr;
     const float *peer[kMaxBatchShards] = {};   // partial vectors of the ranks; entry `rank` is not read

@@ -65,6 +65,14 @@ __global__ __launch_bounds__(kBlock) void k_down(DecodeArgs a)
     stage_down<ROWS, KCH, UB, (FOLD > 0), (FOLD > 0 ? FOLD : 8)>(a, a.s[blockIdx.y], blockIdx.x, gridDim.x, red, a.rf);
 }
 
+// all shards of a batched call, the star reduce folded in: workgroup = ROWS rows of the output, all ranks
+template <int ROWS, int KCH, int UB, bool DOWN>
+__global__ __launch_bounds__(kBlock) void k_rowpar_all(DecodeArgs a, int n_shards)
+{
+    __shared__ float red[ROWS * kWavesPerBlock];
+    stage_rowpar_all<ROWS, KCH, UB, DOWN>(a, n_shards, blockIdx.x, red);
+}
+
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
@@ -150,6 +158,13 @@ hipError_t launch_attn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
     }
     {
         ProfScope ps(kStageOproj, st);
+        if (a.rf.all) {
+            TPI_KCH_SWITCH(a.nq * a.d, {
+                constexpr int ROWS = WIDE ? 8 : 4;
+                hipLaunchKernelGGL((k_rowpar_all<ROWS, KCH, UB, false>), dim3(cdiv(a.h, ROWS)), dim3(kBlock), 0, st, a, n_shards);
+            })
+            return hipGetLastError();
+        }
         TPI_KCH_SWITCH(a.nq * a.d, {
             constexpr int ROWS = WIDE ? 8 : 4;
             int gx = std::max(balanced_grid(cdiv(a.h, ROWS)), cdiv(a.h, kBlock));   // <= 256 rows per workgroup
@@ -175,6 +190,13 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
     }
     {
         ProfScope ps(kStageDown, st);
+        if (a.rf.all) {
+            TPI_KCH_SWITCH(a.sl, {
+                constexpr int ROWS = WIDE ? 8 : 4;
+                hipLaunchKernelGGL((k_rowpar_all<ROWS, KCH, UB, true>), dim3(cdiv(a.h, ROWS)), dim3(kBlock), 0, st, a, n_shards);
+            })
+            return hipGetLastError();
+        }
         TPI_KCH_SWITCH(a.sl, {
             constexpr int ROWS = WIDE ? 8 : 4;
             int gx = std::max(balanced_grid(cdiv(a.h, ROWS)), cdiv(a.h, kBlock));   // <= 256 rows per workgroup

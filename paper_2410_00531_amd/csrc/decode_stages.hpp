@@ -278,6 +278,43 @@ __device__ __forceinline__ void stage_gate_up(const DecodeDims &a, const ShardVi
     st.run(xr, red, rowfn, epi);
 }
 
+// A row-parallel stage for ALL shards of a batched call with the star reduce folded in: the workgroup owns ROWS
+// rows of the output and walks the shards in rank order (unit = shard), each with its own weight rows and its own
+// input vector; a shard's ROWS sums are exactly the partial the one-shard stage stores (same threads, same order of
+// additions), and they are added as the star reduce adds them: ((p0 + p1) + ... + p_{n-1}) + residual.  The
+// partial vectors never go to memory.  DOWN: the down projection (input: the shard's activation), else the output
+// projection (input: the shard's attention output).
+template <int ROWS, int KCH, int UB, bool DOWN>
+__device__ __forceinline__ void stage_rowpar_all(const DecodeArgs &a, int n_shards, int rg, float *red)
+{
+    asm volatile("" ::"s"(a.h), "s"(a.sl), "s"(a.nq), "s"(a.d), "s"(a.ws_act), "s"(a.ws_o), "s"(a.rf.residual), "s"(a.rf.out));
+    const int K = DOWN ? a.sl : a.nq * a.d;
+    const int xoff = DOWN ? a.ws_act : a.ws_o;
+    auto rowfn = [&](int u, const float *(&rows)[ROWS]) {
+        const float *W = DOWN ? a.s[u].w_down : a.s[u].w_o;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) rows[r] = W + (size_t)min(rg * ROWS + r, a.h - 1) * K;
+    };
+    auto xfn = [&](int u, float4 (&x)[KCH]) { load_x_slice<KCH>(a.s[u].ws + xoff, K, x); };
+    RowStreamer<ROWS, KCH, UB> st;
+    st.prefetch(0, 1, n_shards, K, rowfn);
+    float tot[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) tot[r] = 0.f;
+    auto epi = [&](int u, float (&y)[ROWS]) {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) tot[r] = (u == 0) ? y[r] : tot[r] + y[r];
+        if (u == n_shards - 1) {
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const int row = rg * ROWS + r;
+                if (threadIdx.x == r && row < a.h) a.rf.out[row] = tot[r] + a.rf.residual[row];
+            }
+        }
+    };
+    st.run_x(xfn, red, rowfn, epi);
+}
+
 // Stage 5: a unit is ROWS rows of W_down.
 template <int ROWS, int KCH, int UB, bool FOLD, int NP = kMaxBatchShards>
 __device__ __forceinline__ void stage_down(const DecodeDims &a, const ShardView &s, int vwg, int nvwg, float *red,

@@ -90,14 +90,14 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
                          const tpi_kv_layer *kv, int32_t pos, int phase, const float *h_in,
                          float *const *partial_out, void *const *workspace, void *stream,
                          int32_t rf_n = 0, int32_t rf_rank = 0, const float *const *rf_peers = nullptr,
-                         float *rf_out = nullptr)
+                         float *rf_out = nullptr, bool rf_all = false)
 {
     int rc = check_cfg(cfg);
     if (rc) return rc;
     if (phase != TPI_PHASE_ATTN && phase != TPI_PHASE_FFN) return fail(TPI_EINVAL, "unknown phase %d", phase);
     if (n_shards < 1) return fail(TPI_EINVAL, "n_shards %d < 1", n_shards);
     if (n_shards > TPI_MAX_BATCH_SHARDS) return fail(TPI_EINVAL, "n_shards %d > %d", n_shards, TPI_MAX_BATCH_SHARDS);
-    if (!w || !h_in || !partial_out || !workspace) return fail(TPI_EINVAL, "null argument");
+    if (!w || !h_in || (!partial_out && !rf_all) || !workspace) return fail(TPI_EINVAL, "null argument");
     if (phase == TPI_PHASE_ATTN && !kv) return fail(TPI_EINVAL, "kv is null in the attention phase");
     if (pos < 0 || pos >= cfg->max_seq) return fail(TPI_EINVAL, "pos %d outside [0, max_seq %d)", pos, cfg->max_seq);
     if (cfg->dtype != TPI_F32) return fail(TPI_EUNSUPPORTED, "decode is built for fp32 only");
@@ -114,7 +114,12 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
     DecodeArgs a;
     std::memset(&a, 0, sizeof(a));
     fill_decode_dims(cfg, pos, h_in, a);
-    if (rf_n > 0) {
+    if (rf_all) {
+        // every rank's partial is formed by this call: nothing to read from peers
+        if (!rf_out) return fail(TPI_EINVAL, "null argument");
+        if (!aligned16(rf_out)) return fail(TPI_EUNSUPPORTED, "out is not 16-byte aligned");
+        a.rf.n = n_shards; a.rf.rank = 0; a.rf.all = 1; a.rf.residual = h_in; a.rf.out = rf_out;
+    } else if (rf_n > 0) {
         if (rf_n > TPI_MAX_BATCH_SHARDS || rf_rank < 0 || rf_rank >= rf_n)
             return fail(TPI_EINVAL, "n_ranks %d / rank %d out of range (at most %d ranks)", rf_n, rf_rank, TPI_MAX_BATCH_SHARDS);
         if (!rf_out || (rf_n > 1 && !rf_peers)) return fail(TPI_EINVAL, "null argument");
@@ -129,7 +134,8 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
     for (int r = 0; r < n_shards; ++r) {
         const tpi_layer_weights &lw = w[r];
         ShardView &s = a.s[r];
-        if ((!partial_out[r] && rf_n == 0) || !workspace[r]) return fail(TPI_EINVAL, "shard %d: null output or workspace", r);
+        const bool stores_partial = rf_n == 0 && !rf_all;
+        if ((stores_partial && !partial_out[r]) || !workspace[r]) return fail(TPI_EINVAL, "shard %d: null output or workspace", r);
         if (phase == TPI_PHASE_ATTN) {
             if (!lw.attn_norm || !lw.w_qkv || !lw.w_o || !kv[r].k || !kv[r].v)
                 return fail(TPI_EINVAL, "shard %d: null attention weight or cache pointer", r);
@@ -142,14 +148,14 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
             if (!aligned16(lw.ffn_norm) || !aligned16(lw.w_gate) || !aligned16(lw.w_up) || !aligned16(lw.w_down))
                 return fail(TPI_EUNSUPPORTED, "shard %d: pointer not 16-byte aligned", r);
         }
-        if ((rf_n == 0 && !aligned16(partial_out[r])) || !aligned16(workspace[r]))
+        if ((stores_partial && !aligned16(partial_out[r])) || !aligned16(workspace[r]))
             return fail(TPI_EUNSUPPORTED, "shard %d: output or workspace not 16-byte aligned", r);
         s.attn_norm = (const float *)lw.attn_norm; s.w_qkv = (const float *)lw.w_qkv; s.w_o = (const float *)lw.w_o;
         s.ffn_norm = (const float *)lw.ffn_norm; s.w_gate = (const float *)lw.w_gate; s.w_up = (const float *)lw.w_up;
         s.w_down = (const float *)lw.w_down;
         s.k = kv ? (float *)kv[r].k : nullptr;
         s.v = kv ? (float *)kv[r].v : nullptr;
-        s.partial_out = partial_out[r];
+        s.partial_out = stores_partial ? partial_out[r] : nullptr;
         s.ws = (float *)workspace[r];
     }
     hipError_t e = (phase == TPI_PHASE_ATTN) ? launch_attn_phase(a, n_shards, (hipStream_t)stream)
@@ -202,6 +208,14 @@ int tpi_shards_layer_decode(const tpi_shard_cfg *cfg, int32_t n_shards, const tp
                             float *const *host_partial_out, void *const *host_workspace, void *stream)
 {
     return decode_common(cfg, n_shards, host_w, host_kv, pos, phase, h_in, host_partial_out, host_workspace, stream);
+}
+
+int tpi_shards_layer_decode_reduce(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_layer_weights *host_w,
+                                   const tpi_kv_layer *host_kv, int32_t pos, int phase, const float *h_in, float *out,
+                                   void *const *host_workspace, void *stream)
+{
+    return decode_common(cfg, n_shards, host_w, host_kv, pos, phase, h_in, nullptr, host_workspace, stream, 0, 0, nullptr,
+                         out, true);
 }
 
 static int star_reduce_common(const float *const *host_partials, int32_t n, int64_t len, const float *residual,

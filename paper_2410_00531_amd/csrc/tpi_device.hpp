@@ -187,6 +187,57 @@ struct RowStreamer {
             u = nu; b = nb;
         }
     }
+
+    // The same walk for units whose input vectors differ: XFn(unit, float4 (&x)[KCH]) loads the unit's slice.
+    // The next unit's slice is requested right behind that unit's first weight batch, a whole unit before it
+    // is multiplied.
+    template <class XFn, class RowFn, class EpiFn>
+    __device__ __forceinline__ void run_x(XFn &xfn, float *red, RowFn &rowfn, EpiFn &epi)
+    {
+        float acc[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) acc[r] = 0.f;
+        int u = unit, b = 0;
+        if (u >= n_units) return;
+        float4 xc[KCH], xn[KCH];
+        xfn(u, xc);
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) xn[c] = xc[c];
+        while (true) {
+            // current step sits in wa
+            int nu = u, nb = b + 1;
+            if (nb == NB) { nb = 0; nu = u + stride; }
+            bool more = nu < n_units;
+            if (more) {
+                issue(wb, nu, nb, rowfn);
+                if (nb == 0) xfn(nu, xn);
+            }
+            consume(wa, b, xc, acc);
+            if (b == NB - 1) {
+                finish_unit(u, acc, red, epi);
+#pragma unroll
+                for (int c = 0; c < KCH; ++c) xc[c] = xn[c];
+            }
+            if (!more) break;
+            u = nu; b = nb;
+            // current step sits in wb
+            nu = u; nb = b + 1;
+            if (nb == NB) { nb = 0; nu = u + stride; }
+            more = nu < n_units;
+            if (more) {
+                issue(wa, nu, nb, rowfn);
+                if (nb == 0) xfn(nu, xn);
+            }
+            consume(wb, b, xc, acc);
+            if (b == NB - 1) {
+                finish_unit(u, acc, red, epi);
+#pragma unroll
+                for (int c = 0; c < KCH; ++c) xc[c] = xn[c];
+            }
+            if (!more) break;
+            u = nu; b = nb;
+        }
+    }
 };
 
 }  // namespace tpi

@@ -91,6 +91,15 @@ def test_decode_argument_errors():
     n = B.TPI_MAX_BATCH_SHARDS + 1
     assert _code(B.tpi_shards_layer_decode, good, [_w()] * n, [kv] * n, 3, B.TPI_PHASE_ATTN, FAKE,
                  [FAKE] * n, [FAKE] * n, stream=0) == B.TPI_EINVAL
+    # batched variant with the reduce folded in
+    fused = lambda k=2, out=FAKE, h=FAKE, ws=FAKE, pos=3: B.tpi_shards_layer_decode_reduce(
+        good, [_w()] * k, [kv] * k, pos, B.TPI_PHASE_ATTN, h, out, [ws] * k, stream=0)
+    assert _code(fused, k=n) == B.TPI_EINVAL
+    assert _code(fused, out=None) == B.TPI_EINVAL
+    assert _code(fused, h=None) == B.TPI_EINVAL
+    assert _code(fused, ws=None) == B.TPI_EINVAL
+    assert _code(fused, pos=24) == B.TPI_EINVAL
+    assert _code(fused, out=FAKE + 4) == B.TPI_EUNSUPPORTED
 
 
 def test_star_reduce_and_prefill_argument_errors():

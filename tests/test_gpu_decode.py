@@ -209,6 +209,38 @@ def test_reduce_folded_into_the_phase_is_bitwise_the_two_call_sequence():
             assert torch.equal(xin, want)
 
 
+@pytest.mark.parametrize("h,nq,nkv,d,sl,n", [
+    (256, 2, 2, 64, 344, 2),          # tiny
+    (1032, 4, 2, 128, 1000, 5),       # ragged rows: the last row group is short, K not a multiple of 1024
+    (512, 8, 1, 64, 520, 1),          # one rank: the reduce is only the shortcut
+    (8192, 8, 1, 128, 3584, 8),       # the 70B-shaped shard, 8 ranks
+    (4096, 8, 2, 128, 3584, 4),       # the 8B-shaped shard, 4 ranks
+    (264, 2, 1, 96, 5000, B.TPI_MAX_BATCH_SHARDS),
+])
+def test_batched_phase_with_reduce_is_bitwise_the_two_call_sequence(h, nq, nkv, d, sl, n):
+    """tpi_shards_layer_decode_reduce: all ranks' row-parallel products and their star reduce in the last stage's
+    workgroups.  Must equal tpi_shards_layer_decode + tpi_star_reduce bit for bit, and write the same cache slots."""
+    rng = np.random.default_rng(h + n)
+    cfg = B.make_cfg(h, nq, nkv, d, sl, 40)
+    pos = 33
+    data = [random_shard_np(rng, cfg, pos) for _ in range(n)]
+    x = torch.from_numpy(rng.standard_normal(h).astype(np.float32)).cuda()
+    a = [GpuShard(cfg, *dd) for dd in data]
+    b = [GpuShard(cfg, *dd) for dd in data]
+    for phase in (B.TPI_PHASE_ATTN, B.TPI_PHASE_FFN):
+        B.tpi_shards_layer_decode(cfg, [s_.weights for s_ in a], [s_.kv for s_ in a], pos, phase, x,
+                                  [s_.partial for s_ in a], [s_.ws for s_ in a])
+        want = torch.empty(h, device="cuda")
+        B.tpi_star_reduce([s_.partial for s_ in a], x, want)
+        got = torch.full((h,), float("nan"), device="cuda")
+        B.tpi_shards_layer_decode_reduce(cfg, [s_.weights for s_ in b], [s_.kv for s_ in b], pos, phase, x, got,
+                                         [s_.ws for s_ in b])
+        torch.cuda.synchronize()
+        assert torch.equal(got, want)
+        for sa, sb in zip(a, b):
+            assert torch.equal(sa.K, sb.K) and torch.equal(sa.V, sb.V)
+
+
 def test_token_captured_in_a_graph_replays_to_the_eager_result():
     """The decode entry points only enqueue kernels on the caller's stream, so a whole token (phases and
     reduces of several layers, batched and folded variants) can be captured once and replayed.  Every replay,
