@@ -739,7 +739,7 @@ def prefill_leg(args, m, L, N, seed):
 # reads half of the copy's bytes (factor 2.0), WRITE_SIZE all of them (factor 1.0)).  A figure from separate profiler
 # runs of this command, kept in profiles/; None for a workload those runs did not cover.
 MEASURED_GATE_UP_TRAFFIC = {
-    ("llama2-70b-shaped-tp8", 8): {"bytes": round((918720.8 * 2.0 + 450.6 * 1.0) * 1024),
+    ("llama2-70b-shaped-tp8", 8): {"bytes": round((918722.6 * 2.0 + 451.2 * 1.0) * 1024),
                                    "source": "profiles/decode_70b_tp8_eight_shards_per_launch.md"},
 }
 
