@@ -593,39 +593,28 @@ __device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView 
         const float *mp = s.ws + a.ws_att_m + head * kAttnMaxSplits;
         const float *lp = s.ws + a.ws_att_l + head * kAttnMaxSplits;
         const float *ap = s.ws + a.ws_att_acc + (size_t)head * kAttnMaxSplits * d + c * 4;
-        // all loads of a batch are issued before any is used: the partials come from other
-        // compute units' writes, every one of them a trip to memory
+        // every load of the merge is issued before any is used: the partials come from other compute units'
+        // writes, each a trip to memory, and one trip is all the merge should wait for
         float wgt[kAttnMaxSplits], lv[kAttnMaxSplits];
-        float M = -INFINITY;
+        float4 v[kAttnMaxSplits];
 #pragma unroll
         for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
             wgt[sp] = (sp < a.n_splits) ? mp[sp] : -INFINITY;
             lv[sp] = (sp < a.n_splits) ? lp[sp] : 0.f;
+            v[sp] = (sp < a.n_splits) ? *reinterpret_cast<const float4 *>(ap + (size_t)sp * d)
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
         }
+        float M = -INFINITY;
 #pragma unroll
         for (int sp = 0; sp < kAttnMaxSplits; ++sp) M = fmaxf(M, wgt[sp]);
         float L = 0.f;
-#pragma unroll
-        for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
-            wgt[sp] = (sp < a.n_splits) ? __expf(wgt[sp] - M) : 0.f;
-            L = fmaf(wgt[sp], lv[sp], L);
-        }
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int sp0 = 0; sp0 < kAttnMaxSplits; sp0 += 8) {
-            if (sp0 < a.n_splits) {
-                float4 v[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    v[i] = (sp0 + i < a.n_splits) ? *reinterpret_cast<const float4 *>(ap + (size_t)(sp0 + i) * d)
-                                                  : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    float w = wgt[sp0 + i];
-                    o.x = fmaf(w, v[i].x, o.x); o.y = fmaf(w, v[i].y, o.y);
-                    o.z = fmaf(w, v[i].z, o.z); o.w = fmaf(w, v[i].w, o.w);
-                }
-            }
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
+            const float w = (sp < a.n_splits) ? __expf(wgt[sp] - M) : 0.f;
+            L = fmaf(w, lv[sp], L);
+            o.x = fmaf(w, v[sp].x, o.x); o.y = fmaf(w, v[sp].y, o.y);
+            o.z = fmaf(w, v[sp].z, o.z); o.w = fmaf(w, v[sp].w, o.w);
         }
         float inv = 1.0f / L;
         *reinterpret_cast<float4 *>(s.ws + a.ws_o + (size_t)head * d + c * 4) =
