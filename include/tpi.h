@@ -346,6 +346,53 @@ int tpi_window_read_stats(tpi_window *w, double *read_ms);
 int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes);
 
 /*
+ * A host model of the device side of the window, for checking a schedule of
+ * prefetch / acquire / release calls without a GPU.  It models queues that run
+ * in order, events, asynchronous copies and "kernels" that read memory; nothing
+ * runs when it is queued -- tpi_sim_run (and every call of the window that has
+ * to wait) executes what is queued, always picking at random (by `seed`) among
+ * the queues whose next operation may run.  Any order the device could choose,
+ * given queue order and event waits alone, can occur; a reader that is not
+ * ordered after the copy it needs, or a copy not ordered after the readers of
+ * the slot it overwrites, reads the wrong bytes in some of these orders.
+ *
+ * tpi_window_create_blocks_sim / _files_sim: the same windows running on the
+ *   model; every "device" pointer (slots, resident homes) is plain host memory
+ *   and host blocks need not be pinned.  The window must be destroyed before
+ *   the model.  compute_stream arguments of acquire / release are handles from
+ *   tpi_sim_stream (NULL: the model's null stream).
+ * tpi_sim_read: queues a kernel on `stream` that reads [ptr, ptr + bytes) and
+ *   takes cost_ms; when the model executes it, *host_hash receives tpi_sim_hash
+ *   of what it saw and *host_start_ms (nullable) the time it started.  bytes = 0
+ *   queues a kernel that only takes time (an all-reduce, say).
+ * tpi_sim_run: executes everything queued; TPI_ESTATE if operations are left
+ *   that wait for an event nobody recorded.
+ * Time: every queue has a clock in model milliseconds, starting at 0; a copy
+ *   takes bytes / rate (tpi_sim_set_copy_rate, default 1e6 bytes per ms), a
+ *   wait moves the clock up to the recording's time, so the times follow from
+ *   the dependencies alone and not from the order drawn.  tpi_sim_stream_time
+ *   reads a queue's clock.
+ * Calls may come from several host threads.  TPI_EINVAL: null arguments, a
+ * stream of another model.
+ */
+typedef struct tpi_sim tpi_sim;
+int tpi_sim_create(tpi_sim **out, uint64_t seed);
+void *tpi_sim_stream(tpi_sim *sim);
+int tpi_sim_read(tpi_sim *sim, void *stream, const void *ptr, size_t bytes, double cost_ms,
+                 uint64_t *host_hash, double *host_start_ms);
+int tpi_sim_set_copy_rate(tpi_sim *sim, double bytes_per_ms);
+int tpi_sim_stream_time(tpi_sim *sim, void *stream, double *host_ms);
+int tpi_sim_run(tpi_sim *sim);
+uint64_t tpi_sim_hash(const void *ptr, size_t bytes);   /* FNV-1a, 64 bit */
+int tpi_sim_destroy(tpi_sim *sim);
+int tpi_window_create_blocks_sim(tpi_window **out, tpi_sim *sim, int32_t n_blocks,
+                                 const tpi_window_block *blocks, int32_t n_classes,
+                                 const tpi_window_slots *classes);
+int tpi_window_create_files_sim(tpi_window **out, tpi_sim *sim, int32_t n_blocks,
+                                const tpi_window_file_block *blocks, int32_t n_classes,
+                                const tpi_window_slots *classes, int32_t n_staging, int32_t n_readers);
+
+/*
  * The ends of the token loop, run by the master device only (Alg. 1,
  * "Preprocess" and "Postprocess"; Sec. 3.1 Step 4).  All pointers are device
  * pointers; nothing is allocated, nothing synchronises.

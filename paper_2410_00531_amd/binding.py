@@ -32,6 +32,9 @@ EXPORTED = (
     "tpi_last_error", "tpi_abi_version", "tpi_prof_enable", "tpi_prof_read",
     "tpi_decoder_workspace_bytes", "tpi_decoder_create", "tpi_decoder_token", "tpi_decoder_status",
     "tpi_decoder_grid", "tpi_decoder_destroy",
+    "tpi_sim_create", "tpi_sim_stream", "tpi_sim_read", "tpi_sim_run", "tpi_sim_hash", "tpi_sim_destroy",
+    "tpi_sim_set_copy_rate", "tpi_sim_stream_time",
+    "tpi_window_create_blocks_sim", "tpi_window_create_files_sim",
 )
 TPI_STAGE_NONE, TPI_STAGE_QKV, TPI_STAGE_ATTN, TPI_STAGE_OPROJ = 0, 1, 2, 3
 TPI_STAGE_GATE_UP, TPI_STAGE_DOWN, TPI_STAGE_REDUCE, TPI_STAGE_PREFILL_GEMM = 4, 5, 6, 7
@@ -129,6 +132,13 @@ def lib() -> C.CDLL:
         l.tpi_window_create_blocks.restype = C.c_int
         l.tpi_window_create_blocks.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.POINTER(tpi_window_block),
                                                C.c_int32, C.POINTER(tpi_window_slots)]
+        l.tpi_window_create_blocks_sim.restype = C.c_int
+        l.tpi_window_create_blocks_sim.argtypes = [C.POINTER(C.c_void_p), C.c_void_p, C.c_int32, C.POINTER(tpi_window_block),
+                                                   C.c_int32, C.POINTER(tpi_window_slots)]
+        l.tpi_window_create_files_sim.restype = C.c_int
+        l.tpi_window_create_files_sim.argtypes = [C.POINTER(C.c_void_p), C.c_void_p, C.c_int32,
+                                                  C.POINTER(tpi_window_file_block), C.c_int32,
+                                                  C.POINTER(tpi_window_slots), C.c_int32, C.c_int32]
         l.tpi_window_create_files.restype = C.c_int
         l.tpi_window_create_files.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.POINTER(tpi_window_file_block),
                                               C.c_int32, C.POINTER(tpi_window_slots), C.c_int32, C.c_int32]
@@ -397,6 +407,61 @@ def tpi_next_token(logits, u: float, token_out, probs=None, stream=None) -> None
     _check(lib().tpi_next_token(_ptr(logits), logits.numel(), u, _ptr(probs), _ptr(token_out), _stream(stream)))
 
 
+class Sim:
+    """tpi_sim_*: the host model of queues, events and copies that a window can run on instead of the GPU."""
+
+    def __init__(self, seed: int = 0):
+        self._h = C.c_void_p()
+        self._hashes = []          # the model writes into these when it executes the reads
+        l = lib()
+        l.tpi_sim_stream.restype = C.c_void_p
+        l.tpi_sim_stream.argtypes = [C.c_void_p]
+        l.tpi_sim_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_double, C.POINTER(C.c_uint64),
+                                   C.POINTER(C.c_double)]
+        l.tpi_sim_set_copy_rate.argtypes = [C.c_void_p, C.c_double]
+        l.tpi_sim_stream_time.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+        l.tpi_sim_hash.restype = C.c_uint64
+        l.tpi_sim_hash.argtypes = [C.c_void_p, C.c_size_t]
+        l.tpi_sim_run.argtypes = [C.c_void_p]
+        l.tpi_sim_destroy.argtypes = [C.c_void_p]
+        l.tpi_sim_create.argtypes = [C.POINTER(C.c_void_p), C.c_uint64]
+        _check(l.tpi_sim_create(C.byref(self._h), seed))
+
+    def stream(self) -> int:
+        return lib().tpi_sim_stream(self._h)
+
+    def read(self, stream: int, ptr: int, nbytes: int, cost_ms: float = 0.0):
+        """Queues a kernel that reads the range and takes cost_ms; returns (hash cell, start-time cell), filled
+        in once the model has run it."""
+        cell, start = C.c_uint64(0), C.c_double(-1.0)
+        self._hashes.append((cell, start))
+        _check(lib().tpi_sim_read(self._h, stream, ptr, nbytes, cost_ms, C.byref(cell), C.byref(start)))
+        return cell, start
+
+    def set_copy_rate(self, bytes_per_ms: float) -> None:
+        _check(lib().tpi_sim_set_copy_rate(self._h, bytes_per_ms))
+
+    def stream_time(self, stream: int) -> float:
+        ms = C.c_double()
+        _check(lib().tpi_sim_stream_time(self._h, stream, C.byref(ms)))
+        return ms.value
+
+    def run(self) -> None:
+        _check(lib().tpi_sim_run(self._h))
+
+    @staticmethod
+    def hash(ptr: int, nbytes: int) -> int:
+        l = lib()
+        l.tpi_sim_hash.restype = C.c_uint64
+        l.tpi_sim_hash.argtypes = [C.c_void_p, C.c_size_t]
+        return l.tpi_sim_hash(ptr, nbytes)
+
+    def destroy(self) -> None:
+        if self._h:
+            h, self._h = self._h, C.c_void_p()
+            _check(lib().tpi_sim_destroy(h))
+
+
 class Window:
     """tpi_window_* as an object; ``slot(layer)`` mirrors the paper's
     wait_and_release context manager."""
@@ -411,10 +476,12 @@ class Window:
                                        _ptr(device_slots)))
 
     @classmethod
-    def from_blocks(cls, blocks, classes) -> "Window":
+    def from_blocks(cls, blocks, classes, sim: "Optional[Sim]" = None) -> "Window":
         """tpi_window_create_blocks.  blocks: sequence of (host_tensor, nbytes, slot_class, resident) with
         ``resident`` a device tensor / address for a retained block, else None; classes: sequence of
-        (device_tensor, slot_bytes, n_slots).  Block indices then take the place of layer indices."""
+        (device_tensor, slot_bytes, n_slots).  Block indices then take the place of layer indices.
+        With ``sim`` the window runs on that host model (tpi_window_create_blocks_sim): every pointer is
+        then an address in host memory."""
         self = cls.__new__(cls)
         self._h = C.c_void_p()
         self._keep = (list(blocks), list(classes))
@@ -424,11 +491,15 @@ class Window:
         carr = (tpi_window_slots * len(classes))()
         for i, (base, slot_bytes, n_slots) in enumerate(classes):
             carr[i] = tpi_window_slots(_ptr(base), slot_bytes, n_slots)
-        _check(lib().tpi_window_create_blocks(C.byref(self._h), len(blocks), barr, len(classes), carr))
+        if sim is not None:
+            self._keep += (sim,)
+            _check(lib().tpi_window_create_blocks_sim(C.byref(self._h), sim._h, len(blocks), barr, len(classes), carr))
+        else:
+            _check(lib().tpi_window_create_blocks(C.byref(self._h), len(blocks), barr, len(classes), carr))
         return self
 
     @classmethod
-    def from_files(cls, blocks, classes, n_staging: int = 2, n_readers: int = 1) -> "Window":
+    def from_files(cls, blocks, classes, n_staging: int = 2, n_readers: int = 1, sim: "Optional[Sim]" = None) -> "Window":
         """tpi_window_create_files.  blocks: sequence of (path, offset, nbytes, slot_class, resident);
         classes as in from_blocks."""
         self = cls.__new__(cls)
@@ -441,8 +512,13 @@ class Window:
         carr = (tpi_window_slots * len(classes))()
         for i, (base, slot_bytes, n_slots) in enumerate(classes):
             carr[i] = tpi_window_slots(_ptr(base), slot_bytes, n_slots)
-        _check(lib().tpi_window_create_files(C.byref(self._h), len(blocks), barr, len(classes), carr, n_staging,
-                                             n_readers))
+        if sim is not None:
+            self._keep += (sim,)
+            _check(lib().tpi_window_create_files_sim(C.byref(self._h), sim._h, len(blocks), barr, len(classes), carr,
+                                                     n_staging, n_readers))
+        else:
+            _check(lib().tpi_window_create_files(C.byref(self._h), len(blocks), barr, len(classes), carr, n_staging,
+                                                 n_readers))
         return self
 
     def read_ms(self) -> float:

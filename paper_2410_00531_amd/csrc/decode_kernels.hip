@@ -209,10 +209,3 @@ hipError_t launch_ffn_phase(const DecodeArgs &a, int n_shards, hipStream_t st)
 }
 
 }  // namespace tpi
-
-#ifdef TPI_TRACE
-extern "C" int tpi_debug_read_trace(unsigned long long *host_out, int n)
-{
-    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(tpi::g_trace), sizeof(unsigned long long) * n) == hipSuccess ? 0 : -3;
-}
-#endif

@@ -157,7 +157,8 @@ __device__ __forceinline__ void stage_qkv(const DecodeDims &a, const ShardView &
     };
     RowStreamer<ROWS, KCH, UB> st;
     st.prefetch(vwg, nvwg, n_units, a.h, rowfn);
-    if (vwg == 0 && threadIdx.x < a.nkv) s.ws_u32()[a.ws_cnt + threadIdx.x] = 0u;   // attention tickets
+    if (vwg == 0)
+        for (int g = threadIdx.x; g < a.nkv; g += kBlock) s.ws_u32()[a.ws_cnt + g] = 0u;   // attention tickets
     fill_rope_table(a, rope);                      // visible after the barriers inside norm_slice
     float4 xr[KCH];
     const float rinv = norm_slice<KCH>(a.h_in, s.attn_norm, a.h, a.eps, xr, red);
@@ -432,7 +433,6 @@ __device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView 
     const float scale = 1.0f / sqrtf((float)d);
     const int d4 = d / 4;
     const bool e_ok = lane * EPL < d;              // value phase: this lane's elements exist
-    TPI_TRACE_AT(split, 0);
 
     // this lane's slice of every query of the tile (rotated q, scaled once here)
     float4 qv[GT][EPL];
@@ -478,7 +478,6 @@ __device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView 
             for (int i = 0; i < EPL; ++i) vp[i] = 0.f;
             if (e_ok && tw + k < t_end) vr[k] = *reinterpret_cast<const vec_t *>(Vg + (size_t)(tw + k) * d + lane * EPL);
         }
-        TPI_TRACE_AT(split, 1);
         // scores of slot (pass i, row) against every head, in all 16 lanes of the row
         float sc[PASSES][GT];
 #pragma unroll
@@ -493,7 +492,6 @@ __device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView 
                 sc[i][j] = ok ? p : -INFINITY;
             }
         }
-        TPI_TRACE_AT(split, 2);
         // wave-local running softmax: maximum and sum over the wave's 16 slots
 #pragma unroll
         for (int j = 0; j < GT; ++j) {
@@ -516,7 +514,6 @@ __device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView 
 #pragma unroll
             for (int i = 0; i < EPL; ++i) ap[i] *= al;
         }
-        TPI_TRACE_AT(split, 3);
         // values: slot k of the wave = (pass k / 4, row k % 4); its probability sits in lane 16 * row
 #pragma unroll
         for (int k = 0; k < KPW; ++k) {
@@ -530,7 +527,6 @@ __device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView 
             }
         }
     }
-    TPI_TRACE_AT(split, 4);
 
     // the four waves' partials meet in LDS
 #pragma unroll
@@ -572,21 +568,18 @@ __device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView 
     }
     if (total == 1) return;
 
-    // the last workgroup of this KV head to arrive merges the splits.  One thread carries the
-    // release / acquire fences for the workgroup: the barrier before it has drained every wave's
-    // stores to L2, and the barrier after it orders every wave's loads behind the invalidate.
-    TPI_TRACE_AT(split, 5);
+    // the last workgroup of this KV head to arrive merges the splits.  Every thread makes its own partial
+    // stores visible to the device (a workgroup barrier alone orders them only within the workgroup), then
+    // one thread takes the ticket; the merging workgroup's threads each acquire before they read.
+    __threadfence();
     __syncthreads();
     if (tid == 0) {
-        __threadfence();
         unsigned old = atomicAdd(s.ws_u32() + a.ws_cnt + g, 1u);
         s_last = (old == (unsigned)total - 1u);
-        if (s_last) __threadfence();
     }
     __syncthreads();
-    TPI_TRACE_AT(split, 7);
     if (!s_last) return;
-    TPI_TRACE_AT(split, 8);
+    __threadfence();          // acquire: the other workgroups' partials, not a stale cached line
     for (int i = tid; i < G * d4; i += kBlock) {
         int j = i / d4, c = i - j * d4;
         int head = g * G + j;
@@ -620,7 +613,6 @@ __device__ __forceinline__ void stage_attn(const DecodeDims &a, const ShardView 
         *reinterpret_cast<float4 *>(s.ws + a.ws_o + (size_t)head * d + c * 4) =
             make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
     }
-    TPI_TRACE_AT(split, 9);
     if (tid == 0) s.ws_u32()[a.ws_cnt + g] = 0u;  // ready for the next call
 }
 

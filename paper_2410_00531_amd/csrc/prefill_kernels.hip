@@ -23,17 +23,6 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef unsigned short bf16_t;   // storage type
 
-// Development aid, compiled in only with -DTPI_TRACE: thread 0 of a workgroup stamps the 100 MHz wall clock.
-#ifdef TPI_TRACE
-__device__ unsigned long long g_ptrace[1 << 14];
-#define TPI_PTRACE(wg, slot)                                                                 \
-    do {                                                                                     \
-        if (threadIdx.x == 0 && (wg) < 1024) g_ptrace[(wg) * 16 + (slot)] = wall_clock64();  \
-    } while (0)
-#else
-#define TPI_PTRACE(wg, slot) do { } while (0)
-#endif
-
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((unsigned)v << 16); }
 
 // round to nearest, ties to even
@@ -156,7 +145,7 @@ struct GemmArgs {
 // MFMAs); at the end the two waves of a pair exchange halves of their accumulators through LDS and
 // each finishes one of the pair's two row tiles.
 //
-// SWI: the gate | up product with SwiGLU (Eq. 4's activation) applied to the accumulators.  Column
+// SWI: the gate | up product with SwiGLU (the activation of Eq. 2) applied to the accumulators.  Column
 // tile x then covers hidden units 64x .. 64x+63 of BOTH matrices, arranged so that each wave's first
 // 32x32 tile holds gate columns and its second the up columns of the same 32 units: the product
 // silu(gate) * up is taken lane by lane in registers and only the bf16 activation [M][n_split] is
@@ -719,7 +708,6 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
     const bf16_t *Kg = Kc + (size_t)gk * max_seq * D;
     const bf16_t *Vg = Vc + (size_t)gk * max_seq * D;
     bf16_t *Vt = reinterpret_cast<bf16_t *>(smem) + wave * VT;
-    TPI_PTRACE(blockIdx.x, 0);
 
     bf16x8 qf[KS];
     {
@@ -754,7 +742,6 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
         }
     };
     if (wave * TK <= wg_last_key) fetch(wave * TK);
-    TPI_PTRACE(blockIdx.x, 1);
 
     for (int k0 = wave * TK; k0 <= wg_last_key; k0 += 4 * TK) {
         bf16x8 kf[KS];
@@ -777,7 +764,6 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         fetch(min(k0 + 4 * TK, wg_last_key));                     // next round's tile, in flight during this one
-        if (k0 == 0) TPI_PTRACE(blockIdx.x, 2);
 
         f32x16 sacc;
 #pragma unroll
@@ -835,7 +821,6 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
         __builtin_amdgcn_wave_barrier();
     }
 
-    TPI_PTRACE(blockIdx.x, 3);
     // merge the four waves: common maximum, rescale, waves 1..3 hand their partial outputs to wave 0
     if (hb == 0) { ml[0][wave][col] = m_run; ml[1][wave][col] = l_run; }
     __syncthreads();                                              // also: every wave is done with its V tile
@@ -850,7 +835,6 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
     // output tile et (32 elements of every row) is finished by wave et: the other three waves hand it their
     // share through LDS, slot [et][p], p = the source wave's rank among the waves other than et
     float *mg = reinterpret_cast<float *>(smem);
-    TPI_PTRACE(blockIdx.x, 4);
 #pragma unroll
     for (int et = 0; et < ET; ++et) {
         if (wave != et) {
@@ -860,7 +844,6 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
         }
     }
     __syncthreads();
-    TPI_PTRACE(blockIdx.x, 5);
 #pragma unroll
     for (int et = 0; et < ET; ++et) {
         if (wave == et && row_ok) {
@@ -884,7 +867,6 @@ __global__ __launch_bounds__(256) void k_prefill_attn_mfma(AttnArgs a)
             }
         }
     }
-    TPI_PTRACE(blockIdx.x, 6);
 }
 
 // ---------------------------------------------------------------------------
@@ -1093,7 +1075,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 // Tile shape and K split of one GEMM.  128x128 tiles once there are more than 64 rows; when the
-// tiles alone leave most of the 256 compute units idle, smaller tiles, or (where the caller has
+// tiles alone leave most of the compute units idle, smaller tiles, or (where the caller has
 // room for partial products) a split along K.
 struct GemmPlan {
     int bm, bn, splits, k_per_split;
@@ -1104,13 +1086,27 @@ std::atomic<int> g_concurrency{1};   // prefill calls the caller runs side by si
 
 // share: the compute units the call can count on.  The launches pass the current share; the workspace is
 // sized with the whole chip, which gives the largest number of K splits.
-int current_share() { return 256 / std::max(1, g_concurrency.load(std::memory_order_relaxed)); }
+// Compute units of the current device, asked once (256 on an MI355X; also the answer when no device
+// can be asked, so that the size queries stay usable on a host without one).
+int compute_units()
+{
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        return cus;
+    }();
+    return n;
+}
+
+int current_share() { return std::max(1, compute_units() / std::max(1, g_concurrency.load(std::memory_order_relaxed))); }
 
 GemmPlan plan_gemm(int M, int N, int K, int max_splits, int share)
 {
     GemmPlan p{128, 128, 1, cdiv(K, 64) * 64};
     // 128x256 tiles move a quarter less through LDS per flop; they are taken once they still occupy three
-    // quarters of the compute units this call can count on (all 256, or its share when the caller has said
+    // quarters of the compute units this call can count on (all of them, or its share when the caller has said
     // that several prefill calls run side by side on different streams).
     if (max_splits == 1 && M > 64 && N >= 256) {
         if (cdiv(M, 128) * cdiv(N, 256) >= (3 * share) / 4) {
@@ -1417,9 +1413,3 @@ int prefill_launch(const tpi_shard_cfg *c, int S, const tpi_layer_weights *w, co
 
 }  // namespace tpi
 
-#ifdef TPI_TRACE
-extern "C" int tpi_debug_read_ptrace(unsigned long long *host_out, int n)
-{
-    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(tpi::g_ptrace), sizeof(unsigned long long) * n) == hipSuccess ? 0 : -3;
-}
-#endif

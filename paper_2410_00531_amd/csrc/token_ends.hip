@@ -62,9 +62,10 @@ __global__ __launch_bounds__(kChoiceThreads) void k_next_token(const float *__re
     const int chunk = (vocab + kChoiceThreads - 1) / kChoiceThreads;
     const int lo = min(t * chunk, vocab), hi = min(lo + chunk, vocab);
 
-    // largest logit and its lowest index
+    // largest logit and its lowest index.  A range without a logit above -inf (all -inf, or NaN, which
+    // compares as neither) still names its first index, so the token is always inside [0, vocab).
     float best = -INFINITY;
-    int best_i = vocab;
+    int best_i = lo < hi ? lo : vocab;
     for (int i = lo; i < hi; ++i) {
         float z = logits[i];
         if (z > best) { best = z; best_i = i; }

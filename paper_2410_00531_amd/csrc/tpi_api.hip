@@ -111,6 +111,10 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
             return fail(TPI_EUNSUPPORTED, "rows of %lld floats: the GEMV stages are built for at most 16384", (long long)longest);
     }
 
+    // the attention grid has one y index per (KV head, tile of its query heads)
+    if (phase == TPI_PHASE_ATTN && (int64_t)cfg->n_kv_local * ((cfg->n_q_local / cfg->n_kv_local + 7) / 8) > 65535)
+        return fail(TPI_EUNSUPPORTED, "n_kv_local %d: more head tiles than the attention grid can index", cfg->n_kv_local);
+
     DecodeArgs a;
     std::memset(&a, 0, sizeof(a));
     fill_decode_dims(cfg, pos, h_in, a);
@@ -118,6 +122,12 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
         // every rank's partial is formed by this call: nothing to read from peers
         if (!rf_out) return fail(TPI_EINVAL, "null argument");
         if (!aligned16(rf_out)) return fail(TPI_EUNSUPPORTED, "out is not 16-byte aligned");
+        // a workgroup writes its rows of `out` while others still read h_in (as the stage's input or as the shortcut)
+        {
+            const uintptr_t o = reinterpret_cast<uintptr_t>(rf_out), x = reinterpret_cast<uintptr_t>(h_in);
+            const uintptr_t len = (uintptr_t)cfg->hidden * sizeof(float);
+            if (o < x + len && x < o + len) return fail(TPI_EINVAL, "out overlaps h_in");
+        }
         a.rf.n = n_shards; a.rf.rank = 0; a.rf.all = 1; a.rf.residual = h_in; a.rf.out = rf_out;
     } else if (rf_n > 0) {
         if (rf_n > TPI_MAX_BATCH_SHARDS || rf_rank < 0 || rf_rank >= rf_n)

@@ -5,18 +5,6 @@
 
 namespace tpi {
 
-// Development aid, compiled in only with -DTPI_TRACE: thread 0 of a workgroup
-// stamps the 100 MHz wall clock into a global table (slot-major per workgroup).
-#ifdef TPI_TRACE
-__device__ unsigned long long g_trace[1 << 16];   // one definition: include from one source file only
-#define TPI_TRACE_AT(wg, slot)                                                              \
-    do {                                                                                    \
-        if (threadIdx.x == 0 && (wg) < 2048) g_trace[(wg) * 16 + (slot)] = wall_clock64();  \
-    } while (0)
-#else
-#define TPI_TRACE_AT(wg, slot) do { } while (0)
-#endif
-
 constexpr int kWave = 64;
 constexpr int kBlock = 256;              // threads per workgroup of every streaming kernel
 constexpr int kWavesPerBlock = kBlock / kWave;

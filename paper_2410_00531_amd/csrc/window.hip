@@ -1,5 +1,8 @@
-// Sliding window of weight blocks: host runtime over one copy stream and
-// per-slot events (the scheduler of Sec. 3.3 with hipMemcpyAsync as the loader).
+// Sliding window of weight blocks: host runtime over one copy queue and
+// per-slot events (the scheduler of Sec. 3.3 with asynchronous copies as the
+// loader).  The state machine below reaches the device only through
+// WindowEngine (window_engine.hpp): the HIP runtime in production, a host
+// model of streams and events where the ordering itself is under test.
 //
 // A block is a contiguous run of bytes in pinned host memory: a whole layer
 // shard, or -- at the paper's granularity -- one attention block or one FFN
@@ -13,6 +16,7 @@
 
 #include <algorithm>
 #include <cerrno>
+#include <cstdio>
 #include <condition_variable>
 #include <cstring>
 #include <deque>
@@ -24,6 +28,7 @@
 
 #include "../../include/tpi.h"
 #include "host_util.hpp"
+#include "window_engine.hpp"
 
 namespace {
 
@@ -32,8 +37,8 @@ enum SlotState { kEmpty = 0, kPrefetched, kAcquired, kReleased };
 struct Slot {
     int block = -1;
     SlotState state = kEmpty;
-    hipEvent_t ready = nullptr;   // recorded on the copy stream after the slot's copy
-    hipEvent_t freed = nullptr;   // recorded on the compute stream at release
+    void *ready = nullptr;        // recorded on the copy queue after the slot's copy
+    void *freed = nullptr;        // recorded on the compute stream at release
 };
 
 struct Ring {
@@ -63,7 +68,7 @@ struct Block {
     char *resident = nullptr;     // non-null: retained block
     bool loaded = false;          // retained: its one copy has been queued
     int acquired = 0;             // retained: acquire / release pairing
-    hipEvent_t ready = nullptr;   // retained: recorded after the copy
+    void *ready = nullptr;        // retained: recorded after the copy
 };
 
 }  // namespace
@@ -72,25 +77,25 @@ struct Block {
 struct LoadRequest {
     int block = -1;
     void *dst = nullptr;
-    hipEvent_t after = nullptr;   // the copy must wait for this event (previous tenant released), may be null
-    hipEvent_t ready = nullptr;   // recorded on the copy stream after the copy
+    void *after = nullptr;        // the copy must wait for this event (previous tenant released), may be null
+    void *ready = nullptr;        // recorded on the copy queue after the copy
     uint64_t seq = 0;
 };
 
 struct tpi_window {
     std::vector<Block> blocks;
     std::vector<Ring> rings;
-    hipStream_t copy = nullptr;
-    hipEvent_t first_begin = nullptr, last_done = nullptr;   // timing span of the copies
+    tpi::WindowEngine *eng = nullptr;
+    bool owns_engine = false;
+    void *first_begin = nullptr, *last_done = nullptr;       // timing span of the copies
     bool any_copy = false;
     uint64_t bytes_copied = 0;
 
     // file tier
     bool file_tier = false;
-    int device = 0;
     std::vector<int> fds;                    // distinct files, closed at destroy
     std::vector<void *> staging;             // pinned buffers, owned by the window
-    std::vector<hipEvent_t> staging_done;    // the staging buffer's last copy has left it
+    std::vector<void *> staging_done;        // the staging buffer's last copy has left it
     std::vector<char> staging_used;
     size_t staging_bytes = 0;
     int n_readers = 1;                       // threads that share the read of one block
@@ -108,36 +113,115 @@ struct tpi_window {
 
 using tpi::fail;
 
-#define TPI_HIP(call)                                                                              \
+// ---------------------------------------------------------------------------
+// The HIP runtime as the window's engine
+// ---------------------------------------------------------------------------
+namespace tpi {
+namespace {
+
+struct HipEngine final : WindowEngine {
+    hipStream_t copy = nullptr;
+    int device = 0;
+    char text[160] = "";
+
+    int note(hipError_t e, const char *what)
+    {
+        if (e == hipSuccess) return 0;
+        snprintf(text, sizeof(text), "%s: %s", what, hipGetErrorString(e));
+        return 1;
+    }
+    ~HipEngine() override
+    {
+        if (copy) (void)hipStreamDestroy(copy);
+    }
+    void *event_create(bool timing) override
+    {
+        hipEvent_t e = nullptr;
+        if (note(timing ? hipEventCreate(&e) : hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate")) return nullptr;
+        return e;
+    }
+    void event_destroy(void *ev) override { (void)hipEventDestroy((hipEvent_t)ev); }
+    int copy_wait(void *ev) override { return note(hipStreamWaitEvent(copy, (hipEvent_t)ev, 0), "hipStreamWaitEvent"); }
+    int copy_h2d(void *dst, const void *src, size_t bytes) override
+    {
+        return note(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, copy), "hipMemcpyAsync");
+    }
+    int copy_record(void *ev) override { return note(hipEventRecord((hipEvent_t)ev, copy), "hipEventRecord"); }
+    int copy_sync() override { return note(hipStreamSynchronize(copy), "hipStreamSynchronize"); }
+    int stream_wait(void *stream, void *ev) override
+    {
+        return note(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)ev, 0), "hipStreamWaitEvent");
+    }
+    int stream_record(void *stream, void *ev) override { return note(hipEventRecord((hipEvent_t)ev, (hipStream_t)stream), "hipEventRecord"); }
+    int event_sync(void *ev) override { return note(hipEventSynchronize((hipEvent_t)ev), "hipEventSynchronize"); }
+    int elapsed_ms(void *from, void *to, float *ms) override
+    {
+        return note(hipEventElapsedTime(ms, (hipEvent_t)from, (hipEvent_t)to), "hipEventElapsedTime");
+    }
+    void *pinned_alloc(size_t bytes) override
+    {
+        void *p = nullptr;
+        if (note(hipHostMalloc(&p, bytes, hipHostMallocDefault), "hipHostMalloc")) return nullptr;
+        return p;
+    }
+    void pinned_free(void *p) override { (void)hipHostFree(p); }
+    int bind_thread() override { return note(hipSetDevice(device), "hipSetDevice"); }
+    const char *error_text() override { return text; }
+};
+
+}  // namespace
+
+WindowEngine *make_hip_engine()
+{
+    HipEngine *g = new (std::nothrow) HipEngine;
+    if (!g) {
+        fail(TPI_ERUNTIME, "out of host memory");
+        return nullptr;
+    }
+    hipError_t e = hipGetDevice(&g->device);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&g->copy, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+        fail(TPI_ERUNTIME, "window setup: %s", hipGetErrorString(e));
+        delete g;
+        return nullptr;
+    }
+    return g;
+}
+
+}  // namespace tpi
+
+#define TPI_ENG(w, call)                                                                           \
     do {                                                                                           \
-        hipError_t e_ = (call);                                                                    \
-        if (e_ != hipSuccess) return fail(TPI_ERUNTIME, "%s: %s", #call, hipGetErrorString(e_));   \
+        if ((w)->eng->call) return fail(TPI_ERUNTIME, "%s: %s", #call, (w)->eng->error_text());    \
     } while (0)
 
 namespace {
 
 void destroy_objects(tpi_window *w)
 {
-    for (auto e : w->staging_done)
-        if (e) (void)hipEventDestroy(e);
-    for (auto p : w->staging)
-        if (p) (void)hipHostFree(p);
+    tpi::WindowEngine *g = w->eng;
     for (int fd : w->fds)
         if (fd >= 0) ::close(fd);
+    if (!g) return;
+    for (auto e : w->staging_done)
+        if (e) g->event_destroy(e);
+    for (auto p : w->staging)
+        if (p) g->pinned_free(p);
     for (auto &r : w->rings)
         for (auto &s : r.slots) {
-            if (s.ready) (void)hipEventDestroy(s.ready);
-            if (s.freed) (void)hipEventDestroy(s.freed);
+            if (s.ready) g->event_destroy(s.ready);
+            if (s.freed) g->event_destroy(s.freed);
         }
     for (auto &b : w->blocks)
-        if (b.ready) (void)hipEventDestroy(b.ready);
-    if (w->first_begin) (void)hipEventDestroy(w->first_begin);
-    if (w->last_done) (void)hipEventDestroy(w->last_done);
-    if (w->copy) (void)hipStreamDestroy(w->copy);
+        if (b.ready) g->event_destroy(b.ready);
+    if (w->first_begin) g->event_destroy(w->first_begin);
+    if (w->last_done) g->event_destroy(w->last_done);
+    if (w->owns_engine) delete g;
+    w->eng = nullptr;
 }
 
 // `after`: event the copy has to wait for (the slot's previous tenant released), or null.
-int queue_copy(tpi_window *w, int block, void *dst, hipEvent_t after, hipEvent_t ready)
+int queue_copy(tpi_window *w, int block, void *dst, void *after, void *ready)
 {
     const Block &b = w->blocks[block];
     if (w->file_tier) {
@@ -152,11 +236,11 @@ int queue_copy(tpi_window *w, int block, void *dst, hipEvent_t after, hipEvent_t
         w->cv_req.notify_one();
         return TPI_OK;
     }
-    if (after) TPI_HIP(hipStreamWaitEvent(w->copy, after, 0));
-    if (!w->any_copy) TPI_HIP(hipEventRecord(w->first_begin, w->copy));
-    TPI_HIP(hipMemcpyAsync(dst, b.host, b.bytes, hipMemcpyHostToDevice, w->copy));
-    TPI_HIP(hipEventRecord(ready, w->copy));
-    TPI_HIP(hipEventRecord(w->last_done, w->copy));
+    if (after) TPI_ENG(w, copy_wait(after));
+    if (!w->any_copy) TPI_ENG(w, copy_record(w->first_begin));
+    TPI_ENG(w, copy_h2d(dst, b.host, b.bytes));
+    TPI_ENG(w, copy_record(ready));
+    TPI_ENG(w, copy_record(w->last_done));
     w->any_copy = true;
     w->bytes_copied += b.bytes;
     return TPI_OK;
@@ -185,7 +269,8 @@ void loader_fail(tpi_window *w, const std::string &msg)
 // The scheduler's daemon thread: requests are carried out strictly in order.
 void loader_main(tpi_window *w)
 {
-    if (hipSetDevice(w->device) != hipSuccess) { loader_fail(w, "hipSetDevice failed"); return; }
+    tpi::WindowEngine *g = w->eng;
+    if (g->bind_thread()) { loader_fail(w, std::string("loader thread: ") + g->error_text()); return; }
     uint64_t k = 0;
     for (;;) {
         LoadRequest rq;
@@ -199,9 +284,9 @@ void loader_main(tpi_window *w)
         const Block &b = w->blocks[rq.block];
         const int si = (int)(k % w->staging.size());
         k += 1;
-        hipError_t e = hipSuccess;
-        if (w->staging_used[si]) e = hipEventSynchronize(w->staging_done[si]);   // its previous copy has left it
-        if (e != hipSuccess) { loader_fail(w, std::string("hipEventSynchronize: ") + hipGetErrorString(e)); return; }
+        int e = 0;
+        if (w->staging_used[si]) e = g->event_sync(w->staging_done[si]);   // its previous copy has left it
+        if (e) { loader_fail(w, std::string("waiting for a staging buffer: ") + g->error_text()); return; }
         // read the block from its file: n_readers threads, a contiguous part each (this thread takes the first)
         timespec t0, t1;
         clock_gettime(CLOCK_MONOTONIC, &t0);
@@ -231,13 +316,13 @@ void loader_main(tpi_window *w)
         for (const auto &msg : errs)
             if (!msg.empty()) { loader_fail(w, msg); return; }
         clock_gettime(CLOCK_MONOTONIC, &t1);
-        if (rq.after) e = hipStreamWaitEvent(w->copy, rq.after, 0);
-        if (e == hipSuccess && !w->any_copy) e = hipEventRecord(w->first_begin, w->copy);
-        if (e == hipSuccess) e = hipMemcpyAsync(rq.dst, w->staging[si], b.bytes, hipMemcpyHostToDevice, w->copy);
-        if (e == hipSuccess) e = hipEventRecord(rq.ready, w->copy);
-        if (e == hipSuccess) e = hipEventRecord(w->staging_done[si], w->copy);
-        if (e == hipSuccess) e = hipEventRecord(w->last_done, w->copy);
-        if (e != hipSuccess) { loader_fail(w, std::string("copy of a block: ") + hipGetErrorString(e)); return; }
+        if (rq.after) e = g->copy_wait(rq.after);
+        if (!e && !w->any_copy) e = g->copy_record(w->first_begin);
+        if (!e) e = g->copy_h2d(rq.dst, w->staging[si], b.bytes);
+        if (!e) e = g->copy_record(rq.ready);
+        if (!e) e = g->copy_record(w->staging_done[si]);
+        if (!e) e = g->copy_record(w->last_done);
+        if (e) { loader_fail(w, std::string("copy of a block: ") + g->error_text()); return; }
         w->staging_used[si] = 1;
         {
             std::lock_guard<std::mutex> lk(w->mu);
@@ -266,7 +351,7 @@ void stop_loader(tpi_window *w)
 extern "C" {
 
 static int create_common(tpi_window **out, int32_t n_blocks, const tpi_window_block *blocks, int32_t n_classes,
-                         const tpi_window_slots *classes, bool need_host)
+                         const tpi_window_slots *classes, bool need_host, tpi::WindowEngine *borrowed)
 {
     if (!out) return fail(TPI_EINVAL, "out is null");
     *out = nullptr;
@@ -290,18 +375,29 @@ static int create_common(tpi_window **out, int32_t n_blocks, const tpi_window_bl
     }
     tpi_window *w = new (std::nothrow) tpi_window;
     if (!w) return fail(TPI_ERUNTIME, "out of host memory");
+    if (borrowed) {
+        w->eng = borrowed;
+    } else {
+        w->eng = tpi::make_hip_engine();          // sets the error text itself
+        w->owns_engine = true;
+        if (!w->eng) {
+            delete w;
+            return TPI_ERUNTIME;
+        }
+    }
+    tpi::WindowEngine *g = w->eng;
     w->blocks.resize(n_blocks);
     w->rings.resize(n_classes);
-    hipError_t e = hipStreamCreateWithFlags(&w->copy, hipStreamNonBlocking);
+    bool ok = true;
     for (int c = 0; c < n_classes; ++c) {
         Ring &r = w->rings[c];
         r.base = static_cast<char *>(classes[c].base);
         r.slot_bytes = classes[c].slot_bytes;
         r.n_slots = classes[c].n_slots;
         r.slots.resize(r.n_slots);
-        for (int i = 0; e == hipSuccess && i < r.n_slots; ++i) {
-            e = hipEventCreateWithFlags(&r.slots[i].ready, hipEventDisableTiming);
-            if (e == hipSuccess) e = hipEventCreateWithFlags(&r.slots[i].freed, hipEventDisableTiming);
+        for (int i = 0; ok && i < r.n_slots; ++i) {
+            ok = (r.slots[i].ready = g->event_create(false)) != nullptr;
+            if (ok) ok = (r.slots[i].freed = g->event_create(false)) != nullptr;
         }
     }
     for (int i = 0; i < n_blocks; ++i) {
@@ -310,12 +406,12 @@ static int create_common(tpi_window **out, int32_t n_blocks, const tpi_window_bl
         b.bytes = blocks[i].bytes;
         b.cls = blocks[i].slot_class;
         b.resident = blocks[i].retained ? static_cast<char *>(blocks[i].resident) : nullptr;
-        if (b.resident && e == hipSuccess) e = hipEventCreateWithFlags(&b.ready, hipEventDisableTiming);
+        if (b.resident && ok) ok = (b.ready = g->event_create(false)) != nullptr;
     }
-    if (e == hipSuccess) e = hipEventCreate(&w->first_begin);
-    if (e == hipSuccess) e = hipEventCreate(&w->last_done);
-    if (e != hipSuccess) {
-        int rc = fail(TPI_ERUNTIME, "window setup: %s", hipGetErrorString(e));
+    if (ok) ok = (w->first_begin = g->event_create(true)) != nullptr;
+    if (ok) ok = (w->last_done = g->event_create(true)) != nullptr;
+    if (!ok) {
+        int rc = fail(TPI_ERUNTIME, "window setup: %s", g->error_text());
         destroy_objects(w);
         delete w;
         return rc;
@@ -327,11 +423,19 @@ static int create_common(tpi_window **out, int32_t n_blocks, const tpi_window_bl
 int tpi_window_create_blocks(tpi_window **out, int32_t n_blocks, const tpi_window_block *blocks, int32_t n_classes,
                              const tpi_window_slots *classes)
 {
-    return create_common(out, n_blocks, blocks, n_classes, classes, true);
+    return create_common(out, n_blocks, blocks, n_classes, classes, true, nullptr);
 }
 
-int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window_file_block *blocks, int32_t n_classes,
-                            const tpi_window_slots *classes, int32_t n_staging, int32_t n_readers)
+int tpi_window_create_blocks_sim(tpi_window **out, tpi_sim *sim, int32_t n_blocks, const tpi_window_block *blocks,
+                                 int32_t n_classes, const tpi_window_slots *classes)
+{
+    if (!sim) return fail(TPI_EINVAL, "sim is null");
+    return create_common(out, n_blocks, blocks, n_classes, classes, true, tpi_sim_engine(sim));
+}
+
+static int create_files_common(tpi_window **out, int32_t n_blocks, const tpi_window_file_block *blocks, int32_t n_classes,
+                               const tpi_window_slots *classes, int32_t n_staging, int32_t n_readers,
+                               tpi::WindowEngine *borrowed)
 {
     if (!out) return fail(TPI_EINVAL, "out is null");
     *out = nullptr;
@@ -369,7 +473,7 @@ int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window
         fd_of[i] = fds[at];
     }
     tpi_window *w = nullptr;
-    int rc = create_common(&w, n_blocks, plain.data(), n_classes, classes, false);
+    int rc = create_common(&w, n_blocks, plain.data(), n_classes, classes, false, borrowed);
     if (rc != TPI_OK) {
         close_all();
         return rc;
@@ -384,7 +488,6 @@ int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window
         delete w;
         return code;
     };
-    if (hipGetDevice(&w->device) != hipSuccess) return bail(fail(TPI_ERUNTIME, "hipGetDevice failed"));
     w->staging_bytes = largest;
     w->n_readers = n_readers;
     w->staging.assign(n_staging, nullptr);
@@ -392,9 +495,10 @@ int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window
     w->staging_used.assign(n_staging, 0);
     w->issued_seq.assign(n_blocks, 0);
     for (int k = 0; k < n_staging; ++k) {
-        hipError_t e = hipHostMalloc(&w->staging[k], largest, hipHostMallocDefault);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&w->staging_done[k], hipEventDisableTiming);
-        if (e != hipSuccess) return bail(fail(TPI_ERUNTIME, "staging buffers: %s", hipGetErrorString(e)));
+        w->staging[k] = w->eng->pinned_alloc(largest);
+        if (w->staging[k]) w->staging_done[k] = w->eng->event_create(false);
+        if (!w->staging[k] || !w->staging_done[k])
+            return bail(fail(TPI_ERUNTIME, "staging buffers: %s", w->eng->error_text()));
     }
     w->file_tier = true;
     try {
@@ -405,6 +509,19 @@ int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window
     }
     *out = w;
     return TPI_OK;
+}
+
+int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window_file_block *blocks, int32_t n_classes,
+                            const tpi_window_slots *classes, int32_t n_staging, int32_t n_readers)
+{
+    return create_files_common(out, n_blocks, blocks, n_classes, classes, n_staging, n_readers, nullptr);
+}
+
+int tpi_window_create_files_sim(tpi_window **out, tpi_sim *sim, int32_t n_blocks, const tpi_window_file_block *blocks,
+                                int32_t n_classes, const tpi_window_slots *classes, int32_t n_staging, int32_t n_readers)
+{
+    if (!sim) return fail(TPI_EINVAL, "sim is null");
+    return create_files_common(out, n_blocks, blocks, n_classes, classes, n_staging, n_readers, tpi_sim_engine(sim));
 }
 
 int tpi_window_read_stats(tpi_window *w, double *read_ms)
@@ -469,7 +586,7 @@ int tpi_window_acquire(tpi_window *w, int32_t layer, void *compute_stream, const
     if (b.resident) {
         if (!b.loaded) return fail(TPI_ESTATE, "acquire of retained block %d: it was never prefetched", layer);
         if (int rc = wait_issued(w, layer)) return rc;
-        TPI_HIP(hipStreamWaitEvent((hipStream_t)compute_stream, b.ready, 0));
+        TPI_ENG(w, stream_wait(compute_stream, b.ready));
         b.acquired += 1;
         *dev_blob = b.resident;
         return TPI_OK;
@@ -479,7 +596,7 @@ int tpi_window_acquire(tpi_window *w, int32_t layer, void *compute_stream, const
     if (si < 0) return fail(TPI_ESTATE, "acquire of block %d: no prefetched copy of it is in the window", layer);
     Slot &s = r.slots[si];
     if (int rc = wait_issued(w, layer)) return rc;
-    TPI_HIP(hipStreamWaitEvent((hipStream_t)compute_stream, s.ready, 0));
+    TPI_ENG(w, stream_wait(compute_stream, s.ready));
     s.state = kAcquired;
     *dev_blob = r.base + (size_t)si * r.slot_bytes;
     return TPI_OK;
@@ -500,7 +617,7 @@ int tpi_window_release(tpi_window *w, int32_t layer, void *compute_stream)
     const int si = r.find(layer, kAcquired);
     if (si < 0) return fail(TPI_ESTATE, "release of block %d: it was not acquired", layer);
     Slot &s = r.slots[si];
-    TPI_HIP(hipEventRecord(s.freed, (hipStream_t)compute_stream));
+    TPI_ENG(w, stream_record(compute_stream, s.freed));
     s.state = kReleased;
     return TPI_OK;
 }
@@ -520,9 +637,9 @@ int tpi_window_copy_stats(tpi_window *w, double *copy_ms, uint64_t *bytes)
     if (copy_ms) {
         *copy_ms = 0.0;
         if (w->any_copy) {
-            TPI_HIP(hipStreamSynchronize(w->copy));
+            TPI_ENG(w, copy_sync());
             float ms = 0.f;
-            TPI_HIP(hipEventElapsedTime(&ms, w->first_begin, w->last_done));
+            TPI_ENG(w, elapsed_ms(w->first_begin, w->last_done, &ms));
             *copy_ms = ms;
         }
     }
@@ -533,11 +650,11 @@ int tpi_window_destroy(tpi_window *w)
 {
     if (!w) return fail(TPI_EINVAL, "window is null");
     stop_loader(w);
-    hipError_t e = hipStreamSynchronize(w->copy);
+    int rc = TPI_OK;
+    if (w->eng->copy_sync()) rc = fail(TPI_ERUNTIME, "waiting for the copies: %s", w->eng->error_text());
     destroy_objects(w);
     delete w;
-    if (e != hipSuccess) return fail(TPI_ERUNTIME, "hipStreamSynchronize: %s", hipGetErrorString(e));
-    return TPI_OK;
+    return rc;
 }
 
 }  // extern "C"

@@ -100,6 +100,9 @@ def test_decode_argument_errors():
     assert _code(fused, ws=None) == B.TPI_EINVAL
     assert _code(fused, pos=24) == B.TPI_EINVAL
     assert _code(fused, out=FAKE + 4) == B.TPI_EUNSUPPORTED
+    # out must not overlap h_in: other workgroups still read h_in while a workgroup writes its rows of out
+    assert _code(fused, out=FAKE, h=FAKE) == B.TPI_EINVAL and "overlaps" in B.tpi_last_error()
+    assert _code(fused, out=FAKE + 256 * 4 - 16, h=FAKE) == B.TPI_EINVAL and "overlaps" in B.tpi_last_error()
 
 
 def test_star_reduce_and_prefill_argument_errors():
