@@ -344,6 +344,23 @@ def test_70b_shaped_layer_all_shards():
         Kg = shards[r].K.cpu().numpy()
         assert rel_err(Kg[:, pos], kv[r][0][:, pos]) <= FP32_TOL
         assert np.array_equal(Kg[:, :pos], kv[r][0][:, :pos]) and not Kg[:, pos + 1:].any()
+    # The entry point the benchmark's headline step calls, at its full size, directly against the oracle: all 8
+    # shards per launch with both star reduces folded into the row-parallel kernels (the caches take the same
+    # slot again, so the run above does not change its input).
+    ws = [s.weights for s in shards]; kvs = [s.kv for s in shards]; wss = [s.ws for s in shards]
+    for s in shards:
+        s.ws.fill_(float("nan"))
+    h_attn2 = torch.full_like(x, float("nan")); h_out2 = torch.full_like(x, float("nan"))
+    B.tpi_shards_layer_decode_reduce(cfg, ws, kvs, pos, B.TPI_PHASE_ATTN, x, h_attn2, wss)
+    B.tpi_shards_layer_decode_reduce(cfg, ws, None, pos, B.TPI_PHASE_FFN, h_attn2, h_out2, wss)
+    torch.cuda.synchronize()
+    e_attn, e_ffn = rel_err(h_attn2.cpu().numpy(), h_attn), rel_err(h_out2.cpu().numpy(), h_ffn)
+    print(f"70B-shaped layer, 8 shards, KV 1024, reduces folded in: H_attn rel err {e_attn:.2e}, H_ffn {e_ffn:.2e}", flush=True)
+    assert e_attn <= FP32_TOL and e_ffn <= FP32_TOL
+    for r in range(m.n_shards):
+        Kg, Vg = shards[r].K.cpu().numpy(), shards[r].V.cpu().numpy()
+        assert rel_err(Kg[:, pos], kv[r][0][:, pos]) <= FP32_TOL and rel_err(Vg[:, pos], kv[r][1][:, pos]) <= FP32_TOL
+        assert np.array_equal(Kg[:, :pos], kv[r][0][:, :pos]) and not Kg[:, pos + 1:].any()
 
 
 def test_70b_shaped_stack_two_tokens_free_running_and_teacher_forced():

@@ -409,3 +409,64 @@ def test_prefill_attention_with_tiles_shared_by_128_rows(h, nq, nkv, d, sl, n, p
     finally:
         B.tpi_set_prefill_concurrency(1)
 
+
+
+def test_prefill_70b_shaped_8_shards_512_tokens_in_one_call():
+    """What the benchmark's prefill leg times, at its real size: tpi_shards_layer_prefill with all 8 shards of a
+    70B-shaped layer and 512 prompt tokens in ONE call per phase (wide tiles, the divided gate|up launch, the
+    3-way split of the QKV product and the shared-tile attention all at once).  Two of the shards are checked
+    element by element against the oracle (about 10 s of CPU each), every shard's cache must have exactly slots
+    0..511 written, and all shards must agree with their own single-shard call within the bf16 tolerance."""
+    m = configs.LLAMA2_70B_TP8
+    h, nq, nkv, d, sl, N = m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local, m.n_shards
+    n, pos0, max_seq = 512, 0, 520
+    cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq, dtype=B.TPI_BF16)
+    oc = O.ShardCfg(h, nq, nkv, d, sl, max_seq)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(512)
+    shapes = synth.shard_tensor_shapes(h, nq, nkv, d, sl)
+    xt = torch.randn((n, h), generator=gen, device="cuda").to(torch.bfloat16)
+    nws = B.tpi_workspace_bytes(cfg, n) // 4
+    sentinel = 123.0
+    sh = []
+    for r in range(N):
+        wt = {}
+        for name, shp in shapes.items():
+            t = torch.randn(shp, generator=gen, device="cuda", dtype=torch.float32) * synth.WEIGHT_STD
+            wt[name] = (t + 1.0) if name.endswith("_norm") else t.to(torch.bfloat16)
+        K = torch.full((nkv, max_seq, d), sentinel, device="cuda", dtype=torch.bfloat16); V = K.clone()
+        sh.append(dict(wt=wt, W=B.make_weights(wt), K=K, V=V, ws=torch.full((nws,), float("nan"), device="cuda")))
+    checked = (0, N - 1)
+    x = xt.float().cpu().numpy()
+    for phase in (B.TPI_PHASE_ATTN, B.TPI_PHASE_FFN):
+        attn = phase == B.TPI_PHASE_ATTN
+        parts = [torch.full((n, h), float("nan"), device="cuda") for _ in range(N)]
+        B.tpi_shards_layer_prefill(cfg, [s_["W"] for s_ in sh], [B.make_kv(s_["K"], s_["V"]) for s_ in sh] if attn else None,
+                                   pos0, n, phase, xt, parts, [s_["ws"] for s_ in sh])
+        torch.cuda.synchronize()
+        if attn:
+            for r, s_ in enumerate(sh):
+                for t in (s_["K"], s_["V"]):
+                    changed = (t.float() != sentinel).any(dim=2).cpu().numpy()
+                    expect = np.zeros_like(changed); expect[:, pos0:pos0 + n] = True
+                    assert np.array_equal(changed, expect), f"shard {r}: cache slots outside 0..{n - 1} touched, or some not written"
+        # every shard against its own single-shard call (other plans, other attention kernel: tolerance, not bits)
+        one = torch.empty((n, h), device="cuda")
+        ws1 = torch.full((nws,), float("nan"), device="cuda")
+        for r, s_ in enumerate(sh):
+            K1 = torch.full_like(s_["K"], sentinel); V1 = K1.clone()
+            B.tpi_shard_layer_prefill(cfg, s_["W"], B.make_kv(K1, V1) if attn else None, pos0, n, phase, xt, one, ws1)
+            torch.cuda.synchronize()
+            e = rel_err(parts[r].cpu().numpy(), one.cpu().numpy())
+            assert e <= 1e-2, f"shard {r}, phase {phase}: batched vs single call rel err {e:.3e}"
+        for r in checked:
+            w = {k: v.float().cpu().numpy() for k, v in sh[r]["wt"].items()}
+            if attn:
+                Ko = np.zeros((nkv, max_seq, d), np.float32); Vo = np.zeros_like(Ko)
+                ref = O.attn_block(oc, w["attn_norm"], w["w_qkv"], w["w_o"], Ko, Vo, pos0, x)
+                Kg, Vg = sh[r]["K"].float().cpu().numpy(), sh[r]["V"].float().cpu().numpy()
+                assert rel_err(Kg[:, :n], Ko[:, :n]) <= BF16_TOL and rel_err(Vg[:, :n], Vo[:, :n]) <= BF16_TOL
+            else:
+                ref = O.ffn_block(oc, w["ffn_norm"], w["w_gate"], w["w_up"], w["w_down"], x)
+            e = rel_err(parts[r].cpu().numpy(), ref)
+            print(f"70B-shaped prefill, 8 shards x 512 tokens in one call, shard {r}, phase {phase}: rel err {e:.2e}", flush=True)
+            assert e <= BF16_TOL, f"shard {r}, phase {phase}: rel err {e:.3e}"
