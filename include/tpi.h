@@ -53,6 +53,7 @@ enum { TPI_PHASE_ATTN = 1, TPI_PHASE_FFN = 2 };
 #define TPI_ATTN_MAX_SPLITS 32    /* KV-length splits of the decode attention            */
 #define TPI_MAX_BATCH_SHARDS 16   /* shards one batched call can take                    */
 #define TPI_MAX_ROW 16384         /* decode: hidden, ffn_local and n_q_local * head_dim  */
+#define TPI_STATIC_WORKSPACE_BYTES (1u << 20)   /* built-in workspace of tpi_shard_layer_decode_static */
 
 /* Shape of ONE device's shard of one decoder layer (Sec. 3.1 Step 1: attention
  * heads and FFN columns are divided among devices). */
@@ -118,6 +119,25 @@ int tpi_shard_layer_decode(const tpi_shard_cfg *cfg, const tpi_layer_weights *ho
                            const tpi_kv_layer *host_kv, int32_t pos, int phase,
                            const float *h_in, float *partial_out, void *workspace,
                            void *stream);
+
+/*
+ * tpi_shard_layer_decode for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same computation, same kernels and same bits, but the workspace
+ * is a device array inside the library (TPI_STATIC_WORKSPACE_BYTES = 1 MiB per
+ * GPU, held until the process ends) instead of an argument; the call allocates
+ * and frees nothing (the first call on a device looks the array's address up).
+ * TPI_EUNSUPPORTED: tpi_workspace_bytes(cfg, 1) > TPI_STATIC_WORKSPACE_BYTES
+ * (the 70B-shaped shard needs 156 KB).  All calls on one GPU share the one
+ * array: calls that overlap in time on one GPU (different streams, different
+ * threads) race -- queue them on one stream, or give all but one of them
+ * tpi_shard_layer_decode with workspaces of their own.  The array keeps the
+ * last call's contents; nothing in it needs clearing between calls.
+ * Other arguments and errors as for tpi_shard_layer_decode.
+ */
+int tpi_shard_layer_decode_static(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w,
+                                  const tpi_kv_layer *host_kv, int32_t pos, int phase,
+                                  const float *h_in, float *partial_out, void *stream);
 
 /*
  * One phase for one shard with the star reduce and the shortcut folded into

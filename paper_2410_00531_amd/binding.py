@@ -24,7 +24,7 @@ TPI_MAX_BATCH_SHARDS = 16
 
 EXPORTED = (
     "tpi_workspace_bytes", "tpi_shard_layer_decode", "tpi_shards_layer_decode", "tpi_set_prefill_concurrency", "tpi_shards_layer_prefill",
-    "tpi_shard_layer_decode_reduce", "tpi_shards_layer_decode_reduce",
+    "tpi_shard_layer_decode_reduce", "tpi_shards_layer_decode_reduce", "tpi_shard_layer_decode_static",
     "tpi_shard_layer_prefill", "tpi_star_reduce", "tpi_star_reduce_bf16", "tpi_window_create",
     "tpi_window_create_blocks", "tpi_window_create_files", "tpi_window_read_stats", "tpi_window_prefetch",
     "tpi_embed_token", "tpi_lm_head", "tpi_next_token",
@@ -95,6 +95,10 @@ def lib() -> C.CDLL:
         l.tpi_shard_layer_decode.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
                                              C.POINTER(tpi_kv_layer), C.c_int32, C.c_int, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p]
+        l.tpi_shard_layer_decode_static.restype = C.c_int
+        l.tpi_shard_layer_decode_static.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
+                                                    C.POINTER(tpi_kv_layer), C.c_int32, C.c_int, C.c_void_p,
+                                                    C.c_void_p, C.c_void_p]
         l.tpi_shard_layer_decode_reduce.restype = C.c_int
         l.tpi_shard_layer_decode_reduce.argtypes = [C.POINTER(tpi_shard_cfg), C.POINTER(tpi_layer_weights),
                                                     C.POINTER(tpi_kv_layer), C.c_int32, C.c_int, C.c_void_p,
@@ -242,6 +246,13 @@ def tpi_shard_layer_decode(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_
     _check(lib().tpi_shard_layer_decode(C.byref(cfg), C.byref(weights),
                                         C.byref(kv) if kv is not None else None, pos, phase,
                                         _ptr(h_in), _ptr(partial_out), _ptr(workspace), _stream(stream)))
+
+
+def tpi_shard_layer_decode_static(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_layer], pos: int,
+                                  phase: int, h_in, partial_out, stream=None) -> None:
+    _check(lib().tpi_shard_layer_decode_static(C.byref(cfg), C.byref(weights),
+                                               C.byref(kv) if kv is not None else None, pos, phase,
+                                               _ptr(h_in), _ptr(partial_out), _stream(stream)))
 
 
 def tpi_shard_layer_decode_reduce(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_layer], pos: int, phase: int,

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/tpi.h"
 #include "decode_args.hpp"
@@ -17,6 +18,12 @@ static_assert(TPI_MAX_BATCH_SHARDS == tpi::kMaxBatchShards, "limits out of sync"
 static_assert(TPI_ATTN_MAX_SPLITS == tpi::kAttnMaxSplits, "limits out of sync");
 static_assert(TPI_MAX_REDUCE_RANKS == tpi::kMaxReduceRanks, "limits out of sync");
 static_assert(TPI_MAX_HEAD_DIM == 2 * tpi::kRopeHalf, "limits out of sync");
+
+// Workspace of tpi_shard_layer_decode_static: device memory that belongs to the library's code object, one copy
+// per GPU, alive until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// address the kernels get is asked for once per device (scratch_of_current_device).
+constexpr size_t kStaticScratchBytes = TPI_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace tpi {
 
@@ -174,6 +181,27 @@ static int decode_common(const tpi_shard_cfg *cfg, int32_t n_shards, const tpi_l
     return TPI_OK;
 }
 
+// Device address of `scratch` on the current device, asked for on the first call per device.
+static int scratch_of_current_device(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptrs[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(TPI_ERUNTIME, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(TPI_EUNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lk(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(TPI_ERUNTIME, "hipGetSymbolAddress: %s", hipGetErrorString(e));
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return TPI_OK;
+}
+
 }  // namespace tpi
 
 using namespace tpi;
@@ -200,6 +228,27 @@ int tpi_shard_layer_decode(const tpi_shard_cfg *cfg, const tpi_layer_weights *ho
     float *po[1] = {partial_out};
     void *ws[1] = {workspace};
     return decode_common(cfg, 1, host_w, host_kv, pos, phase, h_in, po, ws, stream);
+}
+
+int tpi_shard_layer_decode_static(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w,
+                                  const tpi_kv_layer *host_kv, int32_t pos, int phase, const float *h_in,
+                                  float *partial_out, void *stream)
+{
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    if (cfg->dtype != TPI_F32) return fail(TPI_EUNSUPPORTED, "decode is built for fp32 only");
+    DecodeArgs a;
+    decode_layout(cfg, a);
+    const size_t need = (size_t)a.ws_total * sizeof(float);
+    if (need > kStaticScratchBytes)
+        return fail(TPI_EUNSUPPORTED, "this shard needs %zu bytes of workspace, the built-in one holds %zu: "
+                    "use tpi_shard_layer_decode with a workspace of the caller", need, kStaticScratchBytes);
+    void *ws = nullptr;
+    rc = scratch_of_current_device(&ws);
+    if (rc) return rc;
+    float *po[1] = {partial_out};
+    void *wsv[1] = {ws};
+    return decode_common(cfg, 1, host_w, host_kv, pos, phase, h_in, po, wsv, stream);
 }
 
 int tpi_shard_layer_decode_reduce(const tpi_shard_cfg *cfg, const tpi_layer_weights *host_w,
