@@ -441,25 +441,13 @@ int tpi_next_token(const float *logits, int32_t vocab, float u, float *probs,
 
 /*
  * Whole-token decode of ONE device's shard (Alg. 2, the worker's loop over all
- * decoder layers of one token) in a single persistent launch: per layer the
- * attention block, the star reduce with the shortcut, the FFN block and the
- * second reduce, exactly as the per-phase calls above compute them (bitwise),
- * but the stages of a layer are separated by barriers inside one co-resident
- * grid instead of kernel boundaries, and each reduce is folded into the
- * epilogue of the row-parallel stage before it: this device's partial comes
- * from registers, the other ranks' partials are read from the buffers given
- * at creation (the device's receive buffers; entry `rank` of each table is
- * ignored, n_ranks == 1 needs no tables).
- *
- * workspace: tpi_decoder_workspace_bytes() bytes of device memory, 256-byte
- * aligned, owned by the caller and left to the decoder until destroy.  create
- * uploads the layer table into it and synchronises `stream` once; token only
- * enqueues.  Tokens of one decoder must be queued on one stream at a time.
- * TPI_EUNSUPPORTED: shard shapes the whole-token kernel is not compiled for
- * (the per-phase calls cover every shape).  If a barrier of the kernel ever
- * gives up waiting (it is bounded so that the kernel always ends), the run's
- * output is invalid and tpi_decoder_status() reports TPI_ERUNTIME; status
- * synchronises the stream.
+ * decoder layers of one token) in a single persistent launch.  NOT AVAILABLE in
+ * this build: tpi_decoder_create checks its arguments and returns
+ * TPI_EUNSUPPORTED, tpi_decoder_workspace_bytes returns a token size (0 on a
+ * bad cfg), token / status on a handle return TPI_EUNSUPPORTED.  The names keep
+ * their place in the ABI; the per-phase calls above cover every shape.  (A
+ * chip-wide hand-over between the stages inside one kernel costs more on this
+ * chip than the kernel boundary it replaces -- see the source file.)
  */
 typedef struct tpi_decoder tpi_decoder;
 size_t tpi_decoder_workspace_bytes(const tpi_shard_cfg *cfg, int32_t n_layers);
@@ -489,6 +477,38 @@ enum { TPI_STAGE_NONE = 0, TPI_STAGE_QKV = 1, TPI_STAGE_ATTN = 2, TPI_STAGE_OPRO
        TPI_STAGE_GATE_UP = 4, TPI_STAGE_DOWN = 5, TPI_STAGE_REDUCE = 6, TPI_STAGE_PREFILL_GEMM = 7, TPI_STAGE_TOKEN = 8 };
 int tpi_prof_enable(int stage, int32_t capacity);
 int tpi_prof_read(double *total_ms, int32_t *launches);
+
+/*
+ * Measurement aid (not part of the method): the cost of a hand-over between
+ * two dependent streaming stages on this chip.  256 workgroups stream a buffer
+ * of total_bytes once, cut into segments of segment_kib_per_wave KiB per wave
+ * (2048 waves: 32 KiB per wave = 67 MB per segment); a segment stands for a
+ * stage and may be consumed only once the previous segment's results are
+ * known:
+ *   mode 0  no hand-over (the streaming rate)
+ *   mode 1  hand-over inside the workgroup (through LDS)
+ *   mode 2  hand-over across the chip inside one kernel: results written
+ *           through to memory, a two-level counter tree, one flag per group
+ *           of workgroups, all results read back; requests for the next
+ *           segment's data stay in flight meanwhile (16 KiB per wave)
+ *   mode 3  hand-over by kernel boundary: one launch per segment
+ * The best of `reps` runs is reported.  spread_us: first to last workgroup to
+ * finish a segment; chain_us: from the last workgroup's result to the first
+ * use of the next segment's data (mode 2 only).  results_ok: the exchanged
+ * results were the right ones in every run.
+ * Unlike the entry points of the method this call allocates (total_bytes and
+ * small tables), synchronises `stream` and frees again.
+ * TPI_EINVAL: total_bytes not a multiple of 2048 waves x the segment, segment
+ * not a positive multiple of 16 KiB, more than 4096 segments, mode or reps out
+ * of range; TPI_ERUNTIME: a HIP call failed, or a bounded wait inside the
+ * probe gave up (the kernel still ends).
+ */
+typedef struct tpi_probe_result {
+    double us_total, tb_per_s, us_per_segment, segment_mb, spread_us, chain_us;
+    int32_t segments, results_ok, gave_up;
+} tpi_probe_result;
+int tpi_probe_handover(uint64_t total_bytes, int32_t segment_kib_per_wave, int32_t mode, int32_t reps,
+                       tpi_probe_result *host_out, void *stream);
 
 const char *tpi_last_error(void);
 

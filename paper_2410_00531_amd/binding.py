@@ -33,7 +33,7 @@ EXPORTED = (
     "tpi_decoder_workspace_bytes", "tpi_decoder_create", "tpi_decoder_token", "tpi_decoder_status",
     "tpi_decoder_grid", "tpi_decoder_destroy",
     "tpi_sim_create", "tpi_sim_stream", "tpi_sim_read", "tpi_sim_run", "tpi_sim_hash", "tpi_sim_destroy",
-    "tpi_sim_set_copy_rate", "tpi_sim_stream_time",
+    "tpi_sim_set_copy_rate", "tpi_sim_stream_time", "tpi_probe_handover",
     "tpi_window_create_blocks_sim", "tpi_window_create_files_sim",
 )
 TPI_STAGE_NONE, TPI_STAGE_QKV, TPI_STAGE_ATTN, TPI_STAGE_OPROJ = 0, 1, 2, 3
@@ -416,6 +416,22 @@ def tpi_lm_head(final_norm, w_head, h_in, logits, rms_eps: float = 1e-5, stream=
 def tpi_next_token(logits, u: float, token_out, probs=None, stream=None) -> None:
     """u < 0: largest logit; 0 <= u < 1: inverse CDF at u.  token_out: int32 device tensor of one element."""
     _check(lib().tpi_next_token(_ptr(logits), logits.numel(), u, _ptr(probs), _ptr(token_out), _stream(stream)))
+
+
+class tpi_probe_result(C.Structure):
+    _fields_ = [("us_total", C.c_double), ("tb_per_s", C.c_double), ("us_per_segment", C.c_double),
+                ("segment_mb", C.c_double), ("spread_us", C.c_double), ("chain_us", C.c_double),
+                ("segments", C.c_int32), ("results_ok", C.c_int32), ("gave_up", C.c_int32)]
+
+
+def tpi_probe_handover(total_bytes: int, segment_kib_per_wave: int, mode: int, reps: int = 3, stream=None) -> dict:
+    """Measurement aid: see include/tpi.h.  Returns the result structure as a dict."""
+    l = lib()
+    l.tpi_probe_handover.restype = C.c_int
+    l.tpi_probe_handover.argtypes = [C.c_uint64, C.c_int32, C.c_int32, C.c_int32, C.POINTER(tpi_probe_result), C.c_void_p]
+    r = tpi_probe_result()
+    _check(l.tpi_probe_handover(total_bytes, segment_kib_per_wave, mode, reps, C.byref(r), _stream(stream)))
+    return {k: getattr(r, k) for k, _ in tpi_probe_result._fields_}
 
 
 class Sim:

@@ -1303,6 +1303,16 @@ int prefill_launch(const tpi_shard_cfg *c, int S, const tpi_layer_weights *w, co
     NormArgs na{};
     na.x = (const bf16_t *)h_in; na.h = h; na.eps = c->rms_eps;
     GemmPtrs gp[kMaxPrefillShards];
+    // The hidden state and the norm are replicated on every device (Sec. 3.1): when all shards of the call name the
+    // SAME gain vector -- the emulated devices of one model -- the input is normalised once, into the first shard's
+    // workspace, and every shard's first GEMM reads that one copy (the same values a copy per shard would hold).
+    auto norm_launch = [&](int n_tok) {
+        bool same = S > 1;
+        for (int s = 1; s < S; ++s) same = same && na.g[s] == na.g[0];
+        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n_tok, same ? 1 : S), dim3(256), 0, st, na);
+        if (same)
+            for (int s = 1; s < S; ++s) xn[s] = xn[0];
+    };
 
     if (phase == TPI_PHASE_ATTN) {
         for (int s = 0; s < S; ++s) {
@@ -1315,7 +1325,7 @@ int prefill_launch(const tpi_shard_cfg *c, int S, const tpi_layer_weights *w, co
         if (d > 256) return fail(TPI_EUNSUPPORTED, "head_dim %d > 256", d);
         const int G = nq / nkv;
         if (G > 64) return fail(TPI_EUNSUPPORTED, "more than 64 query heads per KV head");
-        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n, S), dim3(256), 0, st, na);
+        norm_launch(n);
         TPI_LAUNCH_OK();
         int qkv_parts = 1;
         for (int s = 0; s < S; ++s) gp[s] = GemmPtrs{xn[s], (const bf16_t *)w[s].w_qkv, (const bf16_t *)w[s].w_qkv, big[s], nullptr};
@@ -1388,7 +1398,7 @@ int prefill_launch(const tpi_shard_cfg *c, int S, const tpi_layer_weights *w, co
                 return fail(TPI_EUNSUPPORTED, "shard %d: pointer not 16-byte aligned", s);
             na.g[s] = (const float *)w[s].ffn_norm; na.out[s] = xn[s];
         }
-        hipLaunchKernelGGL(k_rmsnorm_bf16, dim3(n, S), dim3(256), 0, st, na);
+        norm_launch(n);
         TPI_LAUNCH_OK();
         for (int s = 0; s < S; ++s) gp[s] = GemmPtrs{xn[s], (const bf16_t *)w[s].w_gate, (const bf16_t *)w[s].w_up, big[s], act[s]};
         if (launch_gemm_swiglu(gp, S, h, sl, h, n, h, st, &e)) {

@@ -165,16 +165,23 @@ def test_prefill_partials_reduce_over_shards():
     assert rel_err(out.cpu().numpy(), O.reduce_f64(refs, x)) <= BF16_TOL
 
 
-@pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0,N", [
-    (512, 4, 1, 64, 1280, 300, 0, 4),      # wide tiles under the batch, gate|up fused
-    (264, 2, 2, 32, 72, 70, 5, 3),         # ragged everything, small tiles, split-K QKV
-    (192, 2, 1, 48, 64, 33, 0, 2),         # head_dim 48: the vector-ALU attention, one shard per launch
-    (256, 2, 1, 64, 128, 40, 2, B.TPI_MAX_BATCH_SHARDS),
+@pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0,N,shared_gains", [
+    (512, 4, 1, 64, 1280, 300, 0, 4, False),      # wide tiles under the batch, gate|up fused
+    (264, 2, 2, 32, 72, 70, 5, 3, False),         # ragged everything, small tiles, split-K QKV
+    (192, 2, 1, 48, 64, 33, 0, 2, False),         # head_dim 48: the vector-ALU attention, one shard per launch
+    (256, 2, 1, 64, 128, 40, 2, B.TPI_MAX_BATCH_SHARDS, False),
+    (512, 4, 1, 64, 1280, 300, 0, 4, True),       # one replicated gain vector: the input is normalised once
+    (264, 2, 2, 32, 72, 70, 5, 3, True),
 ])
-def test_prefill_batched_call_matches_per_shard_calls_and_oracle(h, nq, nkv, d, sl, n, pos0, N):
+def test_prefill_batched_call_matches_per_shard_calls_and_oracle(h, nq, nkv, d, sl, n, pos0, N, shared_gains):
+    _batched_case(h, nq, nkv, d, sl, n, pos0, N, shared_gains)
+
+
+def _batched_case(h, nq, nkv, d, sl, n, pos0, N, shared_gains=False):
     """tpi_shards_layer_prefill: all shards of a layer phase in one set of launches.  Per shard the result must
     agree with the single-shard call (the plans may differ: tolerance, not bits), the cache slots written must be
-    the same set, and shard 0 is checked against the oracle."""
+    the same set, and the first and the last shard are checked against the oracle.  shared_gains: every shard names
+    the same norm gains (the norm is replicated on all devices, Sec. 3.1); the call then normalises once."""
     rng = np.random.default_rng(h + n + N)
     max_seq = pos0 + n + 1
     cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq, dtype=B.TPI_BF16)
@@ -187,6 +194,9 @@ def test_prefill_batched_call_matches_per_shard_calls_and_oracle(h, nq, nkv, d, 
         w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
         wb = {k: (v if k.endswith("_norm") else synth.to_bf16_grid(v)) for k, v in w.items()}
         wt = {k: (torch.from_numpy(v).cuda() if k.endswith("_norm") else _bf16_t(v)) for k, v in wb.items()}
+        if shared_gains and sh:
+            for k in ("attn_norm", "ffn_norm"):
+                wb[k] = sh[0]["wb"][k]; wt[k] = sh[0]["wt"][k]      # the same device tensor: the same pointer
         K = np.full((nkv, max_seq, d), 123.0, np.float32); V = K.copy()
         K[:, :pos0] = synth.to_bf16_grid(rng.standard_normal((nkv, pos0, d)).astype(np.float32))
         V[:, :pos0] = synth.to_bf16_grid(rng.standard_normal((nkv, pos0, d)).astype(np.float32))
@@ -210,12 +220,13 @@ def test_prefill_batched_call_matches_per_shard_calls_and_oracle(h, nq, nkv, d, 
                 assert np.array_equal(ka != s_["K"], kb != s_["K"])          # the same slots written
                 assert rel_err(ka[:, pos0:pos0 + n], kb[:, pos0:pos0 + n]) <= 1e-2
                 assert rel_err(s_["Va"].float().cpu().numpy()[:, pos0:pos0 + n], s_["Vb"].float().cpu().numpy()[:, pos0:pos0 + n]) <= 1e-2
-        w0 = sh[0]["wb"]
-        if attn:
-            ref = O.attn_block(oc, w0["attn_norm"], w0["w_qkv"], w0["w_o"], sh[0]["K"].copy(), sh[0]["V"].copy(), pos0, x)
-        else:
-            ref = O.ffn_block(oc, w0["ffn_norm"], w0["w_gate"], w0["w_up"], w0["w_down"], x)
-        assert rel_err(pa[0].cpu().numpy(), ref) <= BF16_TOL
+        for r in (0, N - 1):
+            w0 = sh[r]["wb"]
+            if attn:
+                ref = O.attn_block(oc, w0["attn_norm"], w0["w_qkv"], w0["w_o"], sh[r]["K"].copy(), sh[r]["V"].copy(), pos0, x)
+            else:
+                ref = O.ffn_block(oc, w0["ffn_norm"], w0["w_gate"], w0["w_up"], w0["w_down"], x)
+            assert rel_err(pa[r].cpu().numpy(), ref) <= BF16_TOL
 
 
 def test_prefill_shards_on_two_streams_equal_one_stream_bitwise():
@@ -363,7 +374,7 @@ def test_prefill_gate_up_divided_between_wide_and_narrow_tiles():
     B.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS)
     try:
         _run_prefill_case(320, 2, 1, 64, 1120, 200, 0, 202, seed=5, attn_scale=4.0)
-        test_prefill_batched_call_matches_per_shard_calls_and_oracle(320, 2, 1, 64, 616, 200, 0, 2)
+        _batched_case(320, 2, 1, 64, 616, 200, 0, 2)
     finally:
         B.tpi_set_prefill_concurrency(1)
 
