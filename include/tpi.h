@@ -192,7 +192,8 @@ int tpi_shards_layer_decode_reduce(const tpi_shard_cfg *cfg, int32_t n_shards,
  * positions pos0 .. pos0+n_tokens-1 with causal attention (token i sees slots
  * 0..pos0+i), filling cache slots pos0..pos0+n_tokens-1 and no others.
  * Weights, h_in [n_tokens][h] and the KV cache are bf16; accumulation is fp32
- * on the matrix cores; partial_out [n_tokens][h] is fp32.
+ * on the matrix cores; partial_out [n_tokens][h] is fp32.  (The decode entry
+ * points take fp32 caches: tpi_kv_widen carries a prefilled cache over.)
  * Errors as for decode; pos0 + n_tokens > max_seq is TPI_EINVAL;
  * cfg.dtype != TPI_BF16 is TPI_EUNSUPPORTED.
  */
@@ -200,6 +201,22 @@ int tpi_shard_layer_prefill(const tpi_shard_cfg *cfg, const tpi_layer_weights *h
                             const tpi_kv_layer *host_kv, int32_t pos0, int32_t n_tokens,
                             int phase, const void *h_in, float *partial_out, void *workspace,
                             void *stream);
+
+/*
+ * From prefill to decode on one cache (Sec. 3.1: the KV cache a device keeps
+ * for its heads serves every later token).  The prefill entry points fill a
+ * bf16 cache and the decode entry points read an fp32 one, so a prompt that
+ * was prefilled through this library continues like this: tpi_kv_widen copies
+ * slots 0 .. n_slots-1 of every local KV head from the bf16 cache
+ * [n_kv_local][src_max_seq][head_dim] into the fp32 cache
+ * [n_kv_local][dst_max_seq][head_dim] (exact: every bf16 value is an fp32
+ * value); slots from n_slots on are left alone.  Decode then appends at
+ * pos = n_slots.  TPI_EINVAL: null pointers, sizes < 1, odd head_dim, n_slots
+ * outside either cache.
+ */
+int tpi_kv_widen(int32_t n_kv_local, int32_t head_dim, int32_t n_slots,
+                 const tpi_kv_layer *host_src_bf16, int32_t src_max_seq,
+                 const tpi_kv_layer *host_dst_f32, int32_t dst_max_seq, void *stream);
 
 /*
  * The same prefill phase for n_shards emulated devices in one set of launches

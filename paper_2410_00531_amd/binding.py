@@ -33,7 +33,7 @@ EXPORTED = (
     "tpi_decoder_workspace_bytes", "tpi_decoder_create", "tpi_decoder_token", "tpi_decoder_status",
     "tpi_decoder_grid", "tpi_decoder_destroy",
     "tpi_sim_create", "tpi_sim_stream", "tpi_sim_read", "tpi_sim_run", "tpi_sim_hash", "tpi_sim_destroy",
-    "tpi_sim_set_copy_rate", "tpi_sim_stream_time", "tpi_probe_handover",
+    "tpi_sim_set_copy_rate", "tpi_sim_stream_time", "tpi_probe_handover", "tpi_kv_widen",
     "tpi_window_create_blocks_sim", "tpi_window_create_files_sim",
 )
 TPI_STAGE_NONE, TPI_STAGE_QKV, TPI_STAGE_ATTN, TPI_STAGE_OPROJ = 0, 1, 2, 3
@@ -246,6 +246,17 @@ def tpi_shard_layer_decode(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_
     _check(lib().tpi_shard_layer_decode(C.byref(cfg), C.byref(weights),
                                         C.byref(kv) if kv is not None else None, pos, phase,
                                         _ptr(h_in), _ptr(partial_out), _ptr(workspace), _stream(stream)))
+
+
+def tpi_kv_widen(src_k, src_v, dst_k, dst_v, n_slots: int, stream=None) -> None:
+    """src_*: bf16 caches [n_kv][src_max_seq][d]; dst_*: fp32 caches [n_kv][dst_max_seq][d] (torch tensors)."""
+    l = lib()
+    l.tpi_kv_widen.restype = C.c_int
+    l.tpi_kv_widen.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(tpi_kv_layer), C.c_int32,
+                               C.POINTER(tpi_kv_layer), C.c_int32, C.c_void_p]
+    n_kv, src_seq, d = src_k.shape
+    src, dst = make_kv(src_k, src_v), make_kv(dst_k, dst_v)
+    _check(l.tpi_kv_widen(n_kv, d, n_slots, C.byref(src), src_seq, C.byref(dst), dst_k.shape[1], _stream(stream)))
 
 
 def tpi_shard_layer_decode_static(cfg, weights: tpi_layer_weights, kv: Optional[tpi_kv_layer], pos: int,

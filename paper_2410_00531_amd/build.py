@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtpi.so")
-SOURCES = ["tpi_api.hip", "decode_kernels.hip", "decode_persistent.hip", "star_reduce.hip", "prefill_kernels.hip", "window.hip", "window_sim.hip", "prof.hip", "probe_handover.hip", "token_ends.hip"]
+SOURCES = ["tpi_api.hip", "decode_kernels.hip", "decode_persistent.hip", "star_reduce.hip", "kv_widen.hip", "prefill_kernels.hip", "window.hip", "window_sim.hip", "prof.hip", "probe_handover.hip", "token_ends.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

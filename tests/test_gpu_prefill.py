@@ -481,3 +481,54 @@ def test_prefill_70b_shaped_8_shards_512_tokens_in_one_call():
             e = rel_err(parts[r].cpu().numpy(), ref)
             print(f"70B-shaped prefill, 8 shards x 512 tokens in one call, shard {r}, phase {phase}: rel err {e:.2e}", flush=True)
             assert e <= BF16_TOL, f"shard {r}, phase {phase}: rel err {e:.3e}"
+
+
+def test_prefill_then_decode_on_one_cache():
+    """Sec. 3.1: the cache a device fills for its heads during the prompt serves every later token.  A prompt goes
+    through the bf16 prefill, tpi_kv_widen carries the cache over to the fp32 cache of the decode entry points
+    (exactly, and nothing beyond the prompt's slots), and the next token's attention phase on that cache agrees
+    with the oracle, which ran the prompt and the token on one cache of its own."""
+    h, nq, nkv, d, sl, n, max_seq = 256, 4, 2, 64, 344, 37, 48
+    rng = np.random.default_rng(21)
+    cfg16 = B.make_cfg(h, nq, nkv, d, sl, max_seq, dtype=B.TPI_BF16)
+    cfg32 = B.make_cfg(h, nq, nkv, d, sl, max_seq + 4)                     # the decode cache may be longer
+    oc = O.ShardCfg(h, nq, nkv, d, sl, max_seq + 4)
+    w = synth.make_layer_shard(rng, h, nq, nkv, d, sl)
+    wb = {k: (v if k.endswith("_norm") else synth.to_bf16_grid(v)) for k, v in w.items()}
+    x = synth.to_bf16_grid(rng.standard_normal((n, h)).astype(np.float32))
+    x_new = rng.standard_normal(h).astype(np.float32)
+    # prompt
+    wt16 = {k: (torch.from_numpy(v).cuda() if k.endswith("_norm") else _bf16_t(v)) for k, v in wb.items()}
+    K16 = torch.zeros((nkv, max_seq, d), device="cuda", dtype=torch.bfloat16); V16 = torch.zeros_like(K16)
+    part = torch.empty((n, h), device="cuda")
+    ws16 = torch.empty(B.tpi_workspace_bytes(cfg16, n) // 4, device="cuda")
+    B.tpi_shard_layer_prefill(cfg16, B.make_weights(wt16), B.make_kv(K16, V16), 0, n, B.TPI_PHASE_ATTN, _bf16_t(x), part, ws16)
+    # carry the cache over
+    sentinel = 7.5
+    K32 = torch.full((nkv, max_seq + 4, d), sentinel, device="cuda"); V32 = torch.full_like(K32, sentinel)
+    B.tpi_kv_widen(K16, V16, K32, V32, n)
+    torch.cuda.synchronize()
+    assert torch.equal(K32[:, :n], K16[:, :n].float()) and torch.equal(V32[:, :n], V16[:, :n].float())
+    assert bool((K32[:, n:] == sentinel).all()) and bool((V32[:, n:] == sentinel).all())
+    # the next token
+    wt32 = {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in wb.items()}
+    out = torch.empty(h, device="cuda")
+    ws32 = torch.empty(B.tpi_workspace_bytes(cfg32, 1) // 4, device="cuda")
+    B.tpi_shard_layer_decode(cfg32, B.make_weights(wt32), B.make_kv(K32, V32), n, B.TPI_PHASE_ATTN,
+                             torch.from_numpy(x_new).cuda(), out, ws32)
+    torch.cuda.synchronize()
+    Ko = np.zeros((nkv, max_seq + 4, d), np.float32); Vo = np.zeros_like(Ko)
+    O.attn_block(oc, wb["attn_norm"], wb["w_qkv"], wb["w_o"], Ko, Vo, 0, x)
+    ref = O.attn_block(oc, wb["attn_norm"], wb["w_qkv"], wb["w_o"], Ko, Vo, n, x_new)
+    e = rel_err(out.cpu().numpy(), ref)
+    assert e <= BF16_TOL, f"token after the prompt: rel err {e:.3e}"
+    assert rel_err(K32[:, n].cpu().numpy(), Ko[:, n]) <= 1e-4       # the new slot is an fp32 one
+
+
+def test_kv_widen_argument_errors():
+    K16 = torch.zeros((2, 8, 64), device="cuda", dtype=torch.bfloat16)
+    K32 = torch.zeros((2, 6, 64), device="cuda")
+    with pytest.raises(B.TpiError) as ei:
+        B.tpi_kv_widen(K16, K16, K32, K32, 7)          # more slots than the fp32 cache has
+    assert ei.value.code == B.TPI_EINVAL
+    B.tpi_kv_widen(K16, K16, K32, K32, 0)              # nothing to do is fine
