@@ -194,6 +194,7 @@ def window_leg(args, m, L, N, blobs, layout, blob_floats, cfg, KV_one, P_all, P_
             setattr(w[0], name, base + layout[name][0] * 4)
         by_ptr[base] = w
     win = B.Window(host, slots, Wn, nbytes)
+    win.calibrate()
     for l in range(Wn):
         win.prefetch(l)
     nxt = [Wn]
@@ -363,6 +364,7 @@ def window_blocks_variant(args, m, L, N, blobs, host, layout, cfg, KV_one, P_all
         blocks.append((host[l][:n_a], n_a * 4, 0, None))
         blocks.append((host[l][n_a:], n_f * 4, 1, blobs[l][0][n_a:] if (2 * l + 1) in retained else None))
     win = B.Window.from_blocks(blocks, [(slots_a, n_a * 4, w // 2), (slots_f, n_f * 4, w // 2)])
+    win.calibrate()
     lib = B.lib()
     stream = torch.cuda.current_stream().cuda_stream
     cfg_p = C.byref(cfg)
@@ -523,6 +525,7 @@ def window_prefill_leg(args, m, seed):
     ref = out_res.clone()
     link_gbps = link_peak()
     win = B.Window([host[l % D] for l in range(L)], slots, Wn, nbytes)
+    copy_streams_tried = win.calibrate()
     for l in range(Wn):
         win.prefetch(l)
     nxt = [Wn]
@@ -546,6 +549,8 @@ def window_prefill_leg(args, m, seed):
         "hidden_fraction": round(min(1.0, 1.0 - (ms_win - ms_res) / copy_ms), 4),
         "copy_stream_effective_gbps": round(win_copy_bytes / (win_copy_ms * 1e-3) / 1e9, 2) if win_copy_ms > 0 else None,
         "windowed_equals_resident_bitwise": same,
+        "copy_streams_tried_by_calibrate": copy_streams_tried,
+        "position_in_process": "last leg, after the decode, prefill and probe legs created their streams",
     }
 
 
@@ -832,14 +837,6 @@ def main():
     cfg = B.make_cfg(m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local, max_seq, m.rms_eps, m.rope_base)
     layout, blob_floats = blob_layout(m)
     assert blob_floats == m.layer_shard_params()
-
-    # ---- the window where PCIe allows hiding: a long prompt through one shard's windowed layers ---
-    # Runs first, on a device that has not yet held the 274 GB stack: window slots allocated after that
-    # stack was freed receive their DMA copies at 36 instead of 57 GB/s (shader accesses are unaffected).
-    want_window_prefill = not args.no_window and not args.no_window_prefill and args.mode == "both"
-    long_prompt = window_prefill_leg(args, m, args.seed) if want_window_prefill else None
-    if want_window_prefill:
-        torch.cuda.empty_cache()
 
     # ---- synthetic stack, drawn on the device (seeded) ------------------------------------------
     gen = torch.Generator(device=dev); gen.manual_seed(args.seed)
@@ -1142,12 +1139,16 @@ def main():
         torch.cuda.empty_cache()
         result["prefill"] = prefill_leg(args, m, L, N, args.seed)
         torch.cuda.empty_cache()
-    if long_prompt is not None:
-        long_prompt["order_dependence"] = (
-            "this leg runs FIRST in the process, before the resident stack is allocated: run after that stack was freed, "
-            "or for some prompt lengths, the window's DMA copies have been seen at 33-40 GB/s instead of the link's "
-            "57 GB/s (cause not found), and hidden_fraction then drops; the figure holds for this order and length")
-        result.setdefault("window", {})["long_prompt_prefill"] = long_prompt
+    # ---- the window where PCIe allows hiding: a long prompt through one shard's windowed layers ---
+    # Runs late in the process on purpose, after many streams have been created: the window picks a copy stream that
+    # does not share a hardware queue with the compute stream (tpi_window_calibrate).  Without that its copies
+    # took turns with the kernels whenever the two streams met on one of the process's four hardware queues.
+    if not args.no_window and not args.no_window_prefill and args.mode == "both":
+        if "blobs" in dir():
+            del blobs, kc, W_all, KV_all, W_one, KV_one
+        torch.cuda.empty_cache()
+        result.setdefault("window", {})["long_prompt_prefill"] = window_prefill_leg(args, m, args.seed)
+        torch.cuda.empty_cache()
     # ---- what a hand-over between dependent stages costs (why one shard per launch stays latency-bound) ----
     if not args.no_handover_probe and args.mode == "both":
         if "blobs" in dir():

@@ -376,6 +376,20 @@ int tpi_window_create_files(tpi_window **out, int32_t n_blocks, const tpi_window
                             int32_t n_classes, const tpi_window_slots *classes, int32_t n_staging,
                             int32_t n_readers);
 int tpi_window_read_stats(tpi_window *w, double *read_ms);
+/*
+ * Optional, once, before the first prefetch: makes sure that the window's
+ * copies overlap with the kernels of compute_stream.  A process has only a few
+ * hardware queues (four here) which its streams share; if the window's copy
+ * stream happens to share one with compute_stream, the marker behind every
+ * copy holds back the kernels queued after it, and copies and compute take
+ * turns instead of overlapping (the window then still computes the right
+ * thing, in compute + copy time).  The call probes for that with a 16 MiB copy
+ * against a 4-byte fill on compute_stream and moves the window to a further
+ * stream until the two are independent (at most 8 tries; *tried, nullable,
+ * receives their number).  It allocates its probe buffers, synchronises both
+ * streams and frees again -- a set-up call.  TPI_ESTATE after a prefetch.
+ */
+int tpi_window_calibrate(tpi_window *w, void *compute_stream, int32_t *tried);
 /* Total time (ms) the copy stream spent in copies between the first prefetch
  * and the last one completed so far, and the bytes requested so far.  Either
  * output may be NULL; asking for the time synchronises the copy stream, asking

@@ -33,7 +33,7 @@ EXPORTED = (
     "tpi_decoder_workspace_bytes", "tpi_decoder_create", "tpi_decoder_token", "tpi_decoder_status",
     "tpi_decoder_grid", "tpi_decoder_destroy",
     "tpi_sim_create", "tpi_sim_stream", "tpi_sim_read", "tpi_sim_run", "tpi_sim_hash", "tpi_sim_destroy",
-    "tpi_sim_set_copy_rate", "tpi_sim_stream_time", "tpi_probe_handover", "tpi_kv_widen",
+    "tpi_sim_set_copy_rate", "tpi_sim_stream_time", "tpi_probe_handover", "tpi_kv_widen", "tpi_window_calibrate",
     "tpi_window_create_blocks_sim", "tpi_window_create_files_sim",
 )
 TPI_STAGE_NONE, TPI_STAGE_QKV, TPI_STAGE_ATTN, TPI_STAGE_OPROJ = 0, 1, 2, 3
@@ -558,6 +558,15 @@ class Window:
             _check(lib().tpi_window_create_files(C.byref(self._h), len(blocks), barr, len(classes), carr, n_staging,
                                                  n_readers))
         return self
+
+    def calibrate(self, stream=None) -> int:
+        """tpi_window_calibrate: returns the number of copy streams tried (1: the first one was independent)."""
+        l = lib()
+        l.tpi_window_calibrate.restype = C.c_int
+        l.tpi_window_calibrate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+        n = C.c_int32(0)
+        _check(l.tpi_window_calibrate(self._h, _stream(stream), C.byref(n)))
+        return n.value
 
     def read_ms(self) -> float:
         ms = C.c_double()

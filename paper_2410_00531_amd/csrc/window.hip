@@ -165,6 +165,58 @@ struct HipEngine final : WindowEngine {
         return p;
     }
     void pinned_free(void *p) override { (void)hipHostFree(p); }
+    // A process has few hardware queues (four here) and its streams share them.  When the copy stream shares one
+    // with the compute stream, the marker that follows a copy holds back the kernels queued behind it and the
+    // copies no longer overlap with compute.  Probe: a 16 MiB copy on the copy stream, then a 4-byte fill on the
+    // compute stream; on queues of their own the fill is done long before the copy.  If not, a further stream is
+    // created (the earlier ones stay alive meanwhile, so that it lands on another queue) and probed, up to 8.
+    int calibrate(void *stream, int *tried) override
+    {
+        constexpr size_t kBytes = (size_t)16 << 20;
+        constexpr int kMaxTries = 8;
+        void *host = nullptr, *dev = nullptr;
+        hipEvent_t c0 = nullptr, c1 = nullptr, t1 = nullptr;
+        hipStream_t rejected[kMaxTries] = {};
+        int n_rejected = 0, rc = 0;
+        *tried = 0;
+        if (note(hipHostMalloc(&host, kBytes, hipHostMallocDefault), "hipHostMalloc")) return 1;
+        rc = note(hipMalloc(&dev, kBytes + 256), "hipMalloc");
+        if (!rc) rc = note(hipEventCreate(&c0), "hipEventCreate");
+        if (!rc) rc = note(hipEventCreate(&c1), "hipEventCreate");
+        if (!rc) rc = note(hipEventCreate(&t1), "hipEventCreate");
+        hipStream_t cs = (hipStream_t)stream;
+        while (!rc) {
+            *tried += 1;
+            float copy_ms = 0.f, fill_ms = 0.f;
+            rc = note(hipStreamSynchronize(cs), "hipStreamSynchronize");
+            if (!rc) rc = note(hipStreamSynchronize(copy), "hipStreamSynchronize");
+            for (int warm = 0; !rc && warm < 2; ++warm) {          // the second pass is the measurement
+                rc = note(hipEventRecord(c0, copy), "hipEventRecord");
+                if (!rc) rc = note(hipMemcpyAsync(dev, host, kBytes, hipMemcpyHostToDevice, copy), "hipMemcpyAsync");
+                if (!rc) rc = note(hipEventRecord(c1, copy), "hipEventRecord");
+                if (!rc) rc = note(hipMemsetAsync(static_cast<char *>(dev) + kBytes, 0, 4, cs), "hipMemsetAsync");
+                if (!rc) rc = note(hipEventRecord(t1, cs), "hipEventRecord");
+                if (!rc) rc = note(hipEventSynchronize(c1), "hipEventSynchronize");
+                if (!rc) rc = note(hipEventSynchronize(t1), "hipEventSynchronize");
+            }
+            if (!rc) rc = note(hipEventElapsedTime(&copy_ms, c0, c1), "hipEventElapsedTime");
+            if (!rc) rc = note(hipEventElapsedTime(&fill_ms, c0, t1), "hipEventElapsedTime");
+            if (rc) break;
+            if (fill_ms < 0.5f * copy_ms || *tried >= kMaxTries) break;     // independent (or out of tries: keep the last)
+            rejected[n_rejected++] = copy;
+            hipStream_t fresh = nullptr;
+            rc = note(hipStreamCreateWithFlags(&fresh, hipStreamNonBlocking), "hipStreamCreateWithFlags");
+            if (rc) { copy = rejected[--n_rejected]; break; }
+            copy = fresh;
+        }
+        for (int i = 0; i < n_rejected; ++i) (void)hipStreamDestroy(rejected[i]);
+        if (c0) (void)hipEventDestroy(c0);
+        if (c1) (void)hipEventDestroy(c1);
+        if (t1) (void)hipEventDestroy(t1);
+        if (dev) (void)hipFree(dev);
+        if (host) (void)hipHostFree(host);
+        return rc;
+    }
     int bind_thread() override { return note(hipSetDevice(device), "hipSetDevice"); }
     const char *error_text() override { return text; }
 };
@@ -619,6 +671,16 @@ int tpi_window_release(tpi_window *w, int32_t layer, void *compute_stream)
     Slot &s = r.slots[si];
     TPI_ENG(w, stream_record(compute_stream, s.freed));
     s.state = kReleased;
+    return TPI_OK;
+}
+
+int tpi_window_calibrate(tpi_window *w, void *compute_stream, int32_t *tried)
+{
+    if (!w) return fail(TPI_EINVAL, "window is null");
+    if (w->any_copy || w->bytes_copied) return fail(TPI_ESTATE, "calibrate belongs before the first prefetch");
+    int n = 0;
+    if (w->eng->calibrate(compute_stream, &n)) return fail(TPI_ERUNTIME, "calibrate: %s", w->eng->error_text());
+    if (tried) *tried = n;
     return TPI_OK;
 }
 

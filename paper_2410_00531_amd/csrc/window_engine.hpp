@@ -29,6 +29,9 @@ struct WindowEngine {
     virtual int elapsed_ms(void *from, void *to, float *ms) = 0;
     virtual void *pinned_alloc(size_t bytes) = 0;                            // staging buffers of the file tier
     virtual void pinned_free(void *p) = 0;
+    // Makes sure that work on the copy queue does not hold back work queued on `stream` afterwards (see
+    // tpi_window_calibrate); *tried receives the number of copy queues tried.  Nothing may be queued on the copy queue.
+    virtual int calibrate(void *stream, int *tried) = 0;
     virtual int bind_thread() = 0;          // called once by the loader thread before it uses the engine
     virtual const char *error_text() = 0;   // of the last call that returned nonzero
 };

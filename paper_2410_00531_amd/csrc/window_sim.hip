@@ -213,6 +213,7 @@ struct tpi_sim final : tpi::WindowEngine {
     }
     void *pinned_alloc(size_t bytes) override { return ::operator new(bytes, std::nothrow); }
     void pinned_free(void *p) override { ::operator delete(p); }
+    int calibrate(void *, int *tried) override { *tried = 1; return 0; }   // the model's queues never share anything
     int bind_thread() override { return 0; }
     const char *error_text() override { return text; }
 };

@@ -527,3 +527,25 @@ def test_measured_window_times_follow_the_scheduler_oracle(pad, T):
     res = subprocess.run([sys.executable, script, str(pad), str(T)], capture_output=True, text=True, timeout=280)
     print(res.stdout[-600:], flush=True)
     assert res.returncode == 0, (res.stdout + res.stderr)[-1500:]
+
+
+def test_window_calibrate_keeps_copies_and_compute_overlapping_in_this_process():
+    """tpi_window_calibrate, in THIS long-lived process (by now it has created many streams, so the window's first
+    copy stream may well share a hardware queue with the compute stream): after the call the compute-bound case
+    must take the time the scheduler oracle predicts, i.e. its copies overlap with the blocks' kernels."""
+    import tpi_window_timing
+    print(tpi_window_timing.run_case(1, 0, calibrate=True), flush=True)
+
+
+def test_window_calibrate_protocol():
+    nfl = 1024
+    host = [torch.zeros(nfl).pin_memory() for _ in range(2)]
+    slots = torch.empty(2 * nfl, device="cuda")
+    win = B.Window(host, slots, 2, nfl * 4)
+    assert 1 <= win.calibrate() <= 8
+    win.prefetch(0)
+    with pytest.raises(B.TpiError) as ei:
+        win.calibrate()
+    assert ei.value.code == B.TPI_ESTATE
+    win.acquire(0); win.release(0)
+    win.destroy()
