@@ -300,16 +300,24 @@ def test_star_reduce_bf16_copy_is_round_to_nearest_even():
     assert ob4.float().tolist() == [1.0, 1.0 + 2.0 ** -6, -1.0, 0.0]
 
 
-def test_prefill_three_layers_two_shards_teacher_forced_and_free_running():
-    """A prompt through a small stack the way bench.py chains the calls (attention phase -> reduce with the
-    bf16 copy -> FFN phase -> reduce), two shards.  The oracle follows the same interface: fp32 hidden state
-    as the shortcut, its bf16 rounding as the next block's input.  Every layer is checked teacher-forced
-    (device layer run from the oracle's input) and the whole chain free-running."""
-    h, nq, nkv, d, sl, n, N, L = 256, 2, 1, 64, 344, 70, 2, 3
+@pytest.mark.parametrize("h,nq,nkv,d,sl,n,N,L,batched", [
+    (256, 2, 1, 64, 344, 70, 2, 3, False),
+    (256, 2, 1, 64, 344, 70, 2, 3, True),
+    (1024, 8, 1, 128, 1792, 512, 2, 8, False),     # an eighth of the 70B-shaped shard's width, the benchmark's prompt length
+    (1024, 8, 1, 128, 1792, 512, 2, 8, True),
+])
+def test_prefill_stack_teacher_forced_and_free_running(h, nq, nkv, d, sl, n, N, L, batched):
+    """A prompt through a stack the way bench.py chains the calls (attention phase -> reduce with the bf16 copy ->
+    FFN phase -> reduce), with one call per shard or all shards per call (batched).  The oracle follows the same
+    interface: fp32 hidden state as the shortcut, its bf16 rounding as the next block's input.  Every layer is
+    checked teacher-forced (device layer run from the oracle's input) and the whole chain free-running: both
+    arrangements must stay inside the bf16 tolerance of the oracle over the whole stack, whatever they differ by
+    from each other."""
     rng = np.random.default_rng(21)
     cfg = B.make_cfg(h, nq, nkv, d, sl, n, dtype=B.TPI_BF16)
     oc = O.ShardCfg(h, nq, nkv, d, sl, n)
     ws = torch.empty(B.tpi_workspace_bytes(cfg, n) // 4, device="cuda")
+    wsb = [torch.empty(B.tpi_workspace_bytes(cfg, n) // 4, device="cuda") for _ in range(N)]
     stack = []
     for l in range(L):
         row = []
@@ -323,15 +331,21 @@ def test_prefill_three_layers_two_shards_teacher_forced_and_free_running():
     def gpu_layer(l, x32_t):
         x16 = x32_t.to(torch.bfloat16)
         parts = [torch.empty((n, h), device="cuda") for _ in range(N)]
-        caches = []
-        for r in range(N):
-            Kt = torch.zeros((nkv, n, d), device="cuda", dtype=torch.bfloat16); Vt = torch.zeros_like(Kt)
-            caches.append((Kt, Vt))
-            B.tpi_shard_layer_prefill(cfg, stack[l][r][2], B.make_kv(Kt, Vt), 0, n, B.TPI_PHASE_ATTN, x16, parts[r], ws)
+        caches = [(torch.zeros((nkv, n, d), device="cuda", dtype=torch.bfloat16),
+                   torch.zeros((nkv, n, d), device="cuda", dtype=torch.bfloat16)) for _ in range(N)]
+        W = [stack[l][r][2] for r in range(N)]
+        if batched:
+            B.tpi_shards_layer_prefill(cfg, W, [B.make_kv(Kt, Vt) for Kt, Vt in caches], 0, n, B.TPI_PHASE_ATTN, x16, parts, wsb)
+        else:
+            for r in range(N):
+                B.tpi_shard_layer_prefill(cfg, W[r], B.make_kv(*caches[r]), 0, n, B.TPI_PHASE_ATTN, x16, parts[r], ws)
         a32 = torch.empty_like(x32_t); a16 = torch.empty_like(x16)
         B.tpi_star_reduce_bf16(parts, x32_t, a32, a16)
-        for r in range(N):
-            B.tpi_shard_layer_prefill(cfg, stack[l][r][2], None, 0, n, B.TPI_PHASE_FFN, a16, parts[r], ws)
+        if batched:
+            B.tpi_shards_layer_prefill(cfg, W, None, 0, n, B.TPI_PHASE_FFN, a16, parts, wsb)
+        else:
+            for r in range(N):
+                B.tpi_shard_layer_prefill(cfg, W[r], None, 0, n, B.TPI_PHASE_FFN, a16, parts[r], ws)
         o32 = torch.empty_like(x32_t); o16 = torch.empty_like(x16)
         B.tpi_star_reduce_bf16(parts, a32, o32, o16)
         torch.cuda.synchronize()
@@ -360,8 +374,8 @@ def test_prefill_three_layers_two_shards_teacher_forced_and_free_running():
         fa, fo = gpu_layer(l, x_gpu)                                           # free-running
         worst_free = max(worst_free, rel_err(fa.cpu().numpy(), ra), rel_err(fo.cpu().numpy(), ro))
         x_orc, x_gpu = ro, fo
-    print(f"prefill stack {L} layers x {N} shards: worst rel err teacher-forced {worst_tf:.2e}, free-running {worst_free:.2e}",
-          flush=True)
+    print(f"prefill stack h={h} n={n}, {L} layers x {N} shards, {'all shards per call' if batched else 'one shard per call'}: "
+          f"worst rel err vs oracle teacher-forced {worst_tf:.2e}, free-running {worst_free:.2e}", flush=True)
     assert worst_tf <= BF16_TOL
     assert worst_free <= BF16_TOL
 
