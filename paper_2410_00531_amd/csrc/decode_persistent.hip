@@ -11,7 +11,7 @@
 // two-level counter tree, a flag per die, the results read back -- takes 3.6-4.2 us from the last workgroup's
 // result to the first use of the next stage's input, on top of 4.5-6 us in which the workgroups of a stage
 // finish one after the other, while a kernel boundary costs 4.5 us all in; weights requested ahead across the
-// hand-over (33 MB in flight) hide about half of it (bench.py --handover-probe; profiles/handover_probe.md).
+// hand-over (33 MB in flight) hide about half of it (tpi_probe_handover; bench.py's handover_probe object).
 // The per-phase entry points cover every shape.
 #include "../../include/tpi.h"
 #include "host_util.hpp"
