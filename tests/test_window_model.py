@@ -150,3 +150,22 @@ def test_hidden_fraction_definition():
     assert M.hidden_fraction(10.0, 10.0, 5.0) == 1.0
     assert M.hidden_fraction(15.0, 10.0, 5.0) == 0.0
     assert M.hidden_fraction(12.5, 10.0, 5.0) == 0.5
+
+
+@pytest.mark.parametrize("h,a,b,s,v,p,L", [(4096, 32, 32, 11008, 32000, 0.25, 32),      # Llama 2-7B over 4 devices
+                                             (8192, 64, 8, 28672, 32000, 0.125, 80)])    # Llama 2-70B over 8
+def test_peak_memory_of_prop_5_is_the_largest_run_of_w_consecutive_blocks(h, a, b, s, v, p, L):
+    """Prop. 5 by brute force: the master walks preprocess, (attention, FFN) x L, postprocess and on into the next
+    token's preprocess; with w blocks resident its peak is the largest total of any w consecutive blocks of that
+    cycle, the worker's the same over its (attention, FFN) x L cycle.  The closed forms must give exactly that."""
+    attn, ffn = M.attn_block_params(h, a, b, p), M.ffn_block_params(h, s, p)
+    master = [M.preprocess_params(h, v)] + [attn, ffn] * L + [M.postprocess_params(h, v)]
+    worker = [attn, ffn] * L
+
+    def brute(cycle, w):
+        n = len(cycle)
+        return max(sum(cycle[(i + k) % n] for k in range(w)) for i in range(n))
+
+    for w in range(1, 9):
+        assert M.peak_master_params(w, h, v, a, b, s, p) == brute(master, w), f"master, w = {w}"
+        assert M.peak_worker_params(w, h, a, b, s, p) == brute(worker, w), f"worker, w = {w}"
