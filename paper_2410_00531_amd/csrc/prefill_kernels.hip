@@ -164,13 +164,15 @@ constexpr int kSwzShift = 1;
 // every load in flight).  Needs whole K-steps (K range a multiple of 64) and the eight-wave tiles.
 // NS = 2 is the same with two stages (step t + 1 requested at the start of step t): half the LDS, so that two
 // workgroups fit a compute unit.
-template <int BM, int BN, int NS, int KW, bool SWI = false, bool DIRECT = false>
-__global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
+template <int BM, int BN, int NS, int KW, bool SWI = false, bool DIRECT = false, int WM = 2>
+__global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
 {
     static_assert(!SWI || BN % 128 == 0, "the fused activation pairs neighbouring 32-column tiles of a wave");
-    static_assert(!DIRECT || (KW == 2 && (NS == 3 || NS == 2)), "the direct loads are written for eight waves and two or three stages");
-    constexpr int BK = 64, NT = 256 * KW;
-    constexpr int MI = BM / 64, NI = BN / 64;           // 32x32 tiles per wave along m and n
+    static_assert(!DIRECT || NS == 3 || NS == 2, "the direct loads are written for two or three stages");
+    static_assert(!DIRECT || KW == 2 || NS == 2, "four waves: two stages, every load waited for in each step");
+    constexpr int BK = 64, NT = 128 * WM * KW;          // WM x 2 waves, KW times
+    constexpr int MI = BM / (32 * WM), NI = BN / 64;    // 32x32 tiles per wave along m and n
+    static_assert(WM == 2 || KW == 1, "the exchange between the waves of a pair is written for 2 x 2 waves");
     constexpr int ACH = BM * (BK / 8) / NT;             // 16-byte chunks per thread, A tile
     constexpr int BCH = BN * (BK / 8) / NT;
     constexpr int STAGE = (BM + BN) * 8;                // chunks per stage
@@ -182,7 +184,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
     extern __shared__ uint4 lds[];                      // 2 * STAGE chunks, sized at launch (not DIRECT)
     __shared__ uint4 stage_a[DIRECT ? STAGE : 1], stage_b[DIRECT ? STAGE : 1], stage_c[DIRECT && NS == 3 ? STAGE : 1];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, kh = tid >> 8;
+    const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) % (2 * WM), kh = tid / (128 * WM);
     const int wm = wave >> 1, wn = wave & 1;
     // Workgroups are dealt to the eight compute dies in turn (linear index mod 8) and every die has its own L2,
     // so the tiles are renumbered: each die works through a contiguous run of (z, band of kRowBand row tiles,
@@ -254,7 +256,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
     const int fr = lane & 31, hb = lane >> 5, sw = (fr >> kSwzShift) & 7;
-    const int a_row = (wm * (BM / 2) + fr) * 8, b_row = (BM + wn * (BN / 2) + fr) * 8;
+    const int a_row = (wm * (BM / WM) + fr) * 8, b_row = (BM + wn * (BN / 2) + fr) * 8;
 
     // the fragments of one K-step (this wave's half of it when KW = 2) out of an LDS stage
     auto multiply = [&](const uint4 *base) {
@@ -279,68 +281,107 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
         const int nsteps = span / BK;                   // whole steps (the launcher checks)
         const int w64 = (tid >> 6) * 64;                // this wave's 8 rows of a 64-row slab, in chunks
         // s_waitcnt immediates: vmcnt in bits 3:0, no wait on the export counter, lgkmcnt 0
-        constexpr int kWaitNext = 0x0070 | (ACH + BCH), kWaitAll = 0x0070;
-        auto request = [&](uint4 *stage, int t) {
+        constexpr int kWaitAll = 0x0070;
+        // One 16-byte-per-lane load from global memory into LDS: the 64 lanes' data go to consecutive LDS addresses
+        // starting at `to` (the same for the whole wave; it travels in M0).  Written out as an instruction rather
+        // than through the compiler's builtin: the compiler counts such a load as one that may return on either of
+        // the memory and LDS counters and from then on waits for EVERY LDS read in flight wherever it needs one of
+        // them, which would undo the read-ahead below.  The waits that these loads need are the explicit ones of
+        // this loop (the count of loads in flight before a barrier, all of them at the end).
+        auto lds_address = [](const uint4 *p) { return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void *)p; };
+        const unsigned w64_bytes = __builtin_amdgcn_readfirstlane(w64 * 16);     // the same for the whole wave: a scalar
+        auto load_to_lds = [&](const bf16_t *from, unsigned at) {
+            unsigned keep;      // M0 belongs to the compiler: it is put back before the statement ends
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                         : "=&s"(keep) : "v"(from), "s"(at) : "memory");
+        };
+        auto request = [&](const uint4 *stage, int t) {
             int kk = k_begin + t * BK + rot;
             if (kk >= k_end) kk -= span;
             const int ko = kk + kc;
+            const unsigned at = lds_address(stage) + w64_bytes;
 #pragma unroll
-            for (int i = 0; i < ACH; ++i)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[i] + ko),
-                                                 (__attribute__((address_space(3))) void *)(stage + i * NT + w64), 16, 0, 0);
+            for (int i = 0; i < ACH; ++i) load_to_lds(pa[i] + ko, at + i * NT * 16);
 #pragma unroll
-            for (int i = 0; i < BCH; ++i)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pb[i] + ko),
-                                                 (__attribute__((address_space(3))) void *)(stage + BM * 8 + i * NT + w64), 16, 0, 0);
+            for (int i = 0; i < BCH; ++i) load_to_lds(pb[i] + ko, at + (BM * 8 + i * NT) * 16);
             __builtin_amdgcn_sched_barrier(0);          // keep the requests ahead of the step's arithmetic
         };
-        // Step t out of `cur` while step t + 2 is requested into `nxt` (last read in step t - 1, before that
-        // step's barrier); at the end this wave's loads of step t + 1 have landed, after the barrier everybody's.
-        // The last two steps request the last step once more (cache hits into a free stage) instead of
-        // nothing, so that the count of loads in flight is the same at every wait.
-        auto direct_step = [&](const uint4 *cur, uint4 *nxt, int t) {
-            request(nxt, min(t + 2, nsteps - 1));
-            multiply(cur);
-            __builtin_amdgcn_s_waitcnt(kWaitNext);
-            __builtin_amdgcn_s_barrier();
+        // A step is four 16-wide slices; a wave multiplies SL of them (its half of the step with eight waves,
+        // all four with four waves).  The fragments of a slice are read from LDS one slice ahead of the matrix
+        // instructions that use them, into a second set of registers: while the matrix cores work through the
+        // products of one slice, the next slice's reads are already on their way, also across the barrier between
+        // two steps -- the first slice of step t + 1 is read right after the barrier that makes step t + 1 visible
+        // and is used only after the last slice of step t has been multiplied.  The order of the products per
+        // accumulator is unchanged.
+        constexpr int SL = BK / 16 / KW;
+        static_assert(SL == 2 || SL == 4, "an even number of slices: the two fragment sets alternate");
+        bf16x8 fa0[MI], fb0[NI], fa1[MI], fb1[NI];
+        auto read_slice = [&](const uint4 *base, int s0, bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) {
+            const int ch = (2 * (kh * SL + s0) + hb) ^ sw;
+#pragma unroll
+            for (int a = 0; a < MI; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(base + a_row + a * 32 * 8 + ch);
+#pragma unroll
+            for (int b = 0; b < NI; ++b) fb[b] = *reinterpret_cast<const bf16x8 *>(base + b_row + b * 32 * 8 + ch);
+            __builtin_amdgcn_sched_barrier(0);          // the reads stay ahead of the products that follow
         };
-        if constexpr (NS == 2) {
-            // two stages (half the LDS: two workgroups per compute unit): step t + 1 is requested at the start of
-            // step t into the stage that step t - 1 was read from, and must have landed at the end of step t
-            auto step2 = [&](const uint4 *cur, uint4 *nxt, int t) {
-                request(nxt, min(t + 1, nsteps - 1));
-                multiply(cur);
-                __builtin_amdgcn_s_waitcnt(kWaitAll);
-                __builtin_amdgcn_s_barrier();
-            };
-            request(stage_a, 0);
-            __builtin_amdgcn_s_waitcnt(kWaitAll);
-            __builtin_amdgcn_s_barrier();
-            int t = 0;
-            for (; t + 2 <= nsteps; t += 2) {
-                step2(stage_a, stage_b, t);
-                step2(stage_b, stage_a, t + 1);
+        auto multiply_slice = [&](const bf16x8 (&fa)[MI], const bf16x8 (&fb)[NI]) {
+#pragma unroll
+            for (int a = 0; a < MI; ++a)
+#pragma unroll
+                for (int b = 0; b < NI; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // Step t out of `cur`; its first slice is in fa0 / fb0 already.  Before the barrier this wave's loads of
+        // step t + 1 have landed (kWaitStep leaves the younger requests in flight) and its reads of `cur` have
+        // returned; after the barrier everybody's, so `cur` is free and takes step t + NS at once -- a request has
+        // NS - 1 whole steps to land -- and the first slice of step t + 1 is read from `nxt`.
+        // The last steps request the last step once more (cache hits into a free stage) instead of nothing, so
+        // that the count of loads in flight is the same at every wait; the slice read after the last step's
+        // barrier comes from such a repeat and is not used.
+        constexpr int kWaitStep = 0x0070 | ((NS - 2) * (ACH + BCH)), kWaitFirst = 0x0070 | ((NS - 1) * (ACH + BCH));
+        static_assert((NS - 1) * (ACH + BCH) <= 15, "the count of loads in flight has four bits in the immediate");
+        auto direct_step = [&](uint4 *cur, const uint4 *nxt, int t) {
+            read_slice(cur, 1, fa1, fb1);
+            multiply_slice(fa0, fb0);
+            if constexpr (SL == 4) {
+                read_slice(cur, 2, fa0, fb0);
+                multiply_slice(fa1, fb1);
+                read_slice(cur, 3, fa1, fb1);
+                multiply_slice(fa0, fb0);
             }
-            if (t < nsteps) step2(stage_a, stage_b, t++);
-        } else {
+            __builtin_amdgcn_s_waitcnt(kWaitStep);
+            __builtin_amdgcn_s_barrier();
+            request(cur, min(t + NS, nsteps - 1));
+            read_slice(nxt, 0, fa0, fb0);
+            multiply_slice(fa1, fb1);
+        };
         request(stage_a, 0);
         request(stage_b, min(1, nsteps - 1));
-        __builtin_amdgcn_s_waitcnt(kWaitNext);
+        if constexpr (NS == 3) request(stage_c, min(2, nsteps - 1));
+        __builtin_amdgcn_s_waitcnt(kWaitFirst);
         __builtin_amdgcn_s_barrier();
-        // whole rounds of three steps (a loop with exits between the steps makes the compiler add a wait for
-        // all loads in flight at its head); every round ends where it began, so the one or two steps left
-        // over start in the first stage again
+        read_slice(stage_a, 0, fa0, fb0);
+        // whole rounds of NS steps (a loop with exits between the steps makes the compiler add waits of its own at
+        // its head); every round ends where it began, so the steps left over start in the first stage again
         int t = 0;
-        for (; t + 3 <= nsteps; t += 3) {
-            direct_step(stage_a, stage_c, t);
-            direct_step(stage_b, stage_a, t + 1);
-            direct_step(stage_c, stage_b, t + 2);
+        if constexpr (NS == 2) {
+            for (; t + 2 <= nsteps; t += 2) {
+                direct_step(stage_a, stage_b, t);
+                direct_step(stage_b, stage_a, t + 1);
+            }
+            if (t < nsteps) direct_step(stage_a, stage_b, t++);
+        } else {
+            for (; t + 3 <= nsteps; t += 3) {
+                direct_step(stage_a, stage_b, t);
+                direct_step(stage_b, stage_c, t + 1);
+                direct_step(stage_c, stage_a, t + 2);
+            }
+            if (t < nsteps) direct_step(stage_a, stage_b, t++);
+            if (t < nsteps) direct_step(stage_b, stage_c, t++);
         }
-        if (t < nsteps) direct_step(stage_a, stage_c, t++);
-        if (t < nsteps) direct_step(stage_b, stage_a, t++);
-        __builtin_amdgcn_s_waitcnt(kWaitAll);           // the repeated requests, before the stages are reused
+        __builtin_amdgcn_s_waitcnt(kWaitAll);           // the repeated requests and the unused slice, before the stages are reused
         __builtin_amdgcn_s_barrier();
-        }
     } else {
         uint4 ring[NS][ACH + BCH];
         auto load_tiles = [&](auto J, int k0) {
@@ -439,7 +480,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
                 const int unit = bx * (BN / 2) + wn * (BN / 4) + c * 32 + (lane & 31);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    int row = m0 + wm * (BM / WM) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     const float gt = acc[a][2 * c][r], up = acc[a][2 * c + 1][r];
                     if (row < g.M && unit < g.n_split) P.act[(size_t)row * g.ldc + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
                 }
@@ -450,7 +491,7 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
                 int col = n0 + wn * (BN / 2) + b * 32 + (lane & 31);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    int row = m0 + wm * (BM / 2) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    int row = m0 + wm * (BM / WM) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     if (row < g.M && col < g.N) C[(size_t)row * g.ldc + col] = acc[a][b][r];
                 }
             }
@@ -477,7 +518,9 @@ __global__ __launch_bounds__(256 * KW) void k_gemm_bf16_nt(GemmArgs g)
         else finish(std::integral_constant<int, 1>{});
     } else {
         finish(std::integral_constant<int, 0>{});
-        if constexpr (MI == 2) finish(std::integral_constant<int, 1>{});
+        if constexpr (MI >= 2) finish(std::integral_constant<int, 1>{});
+        if constexpr (MI >= 3) finish(std::integral_constant<int, 2>{});
+        if constexpr (MI >= 4) finish(std::integral_constant<int, 3>{});
     }
 }
 
@@ -1154,13 +1197,13 @@ PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
 }
 
 // Launches one instantiation with its LDS size; above 64 KB the kernel has to opt in once per device.
-template <int BM, int BN, int NS, int KW, bool SWI, bool DIRECT = false>
+template <int BM, int BN, int NS, int KW, bool SWI, bool DIRECT = false, int WM = 2>
 hipError_t launch_gemm_kernel(dim3 grid, const GemmArgs &g, hipStream_t st)
 {
     // DIRECT: the stages are static arrays of the kernel
     constexpr size_t lds = DIRECT ? 0 : (size_t)2 * (BM + BN) * 8 * 16;
     constexpr size_t lds_total = DIRECT ? (size_t)NS * (BM + BN) * 8 * 16 : lds;
-    auto *kern = k_gemm_bf16_nt<BM, BN, NS, KW, SWI, DIRECT>;
+    auto *kern = k_gemm_bf16_nt<BM, BN, NS, KW, SWI, DIRECT, WM>;
     if constexpr (lds_total > 65536) {
         static std::atomic<bool> opted[64];
         int dev = 0;
@@ -1173,12 +1216,22 @@ hipError_t launch_gemm_kernel(dim3 grid, const GemmArgs &g, hipStream_t st)
             opted[dev].store(true, std::memory_order_release);
         }
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256 * KW), lds, st, g);
+    hipLaunchKernelGGL(kern, grid, dim3(128 * WM * KW), lds, st, g);
     return hipGetLastError();
 }
 
 // The eight-wave tiles load straight into LDS when every K range is whole 64-element steps.
 inline bool direct_ok(const GemmArgs &g) { return g.K % 64 == 0 && g.k_per_split % 64 == 0; }
+
+// 256x256 tiles (four waves, each a 128x128 quarter) fetch a third less per flop from L2 and from LDS than
+// 128x256 tiles.  They are taken when there are at least two row tiles' worth of rows and the tiles fill the
+// compute units this call can count on to at least four fifths, counted over whole rounds.
+inline bool square_tiles_pay(int M, int col_tiles, int S)
+{
+    const long cus = std::max(1, current_share()), tiles = (long)cdiv(M, 256) * col_tiles * S;
+    const long rounds = (tiles + cus - 1) / cus;
+    return M > 128 && tiles >= cus && 5 * tiles >= 4 * rounds * cus;
+}
 
 // max_splits > 1: C must have room for that many partial products of M * ldc floats; the number
 // actually written is returned in *n_parts.
@@ -1195,9 +1248,12 @@ hipError_t launch_gemm(const GemmPtrs *ptrs, int S, int lda, int n_split, int ld
     for (int s = 0; s < S; ++s) g.p[s] = ptrs[s];
     ProfScope ps(kStagePrefillGemm, st);
     dim3 grid(cdiv(N, p.bn), cdiv(M, p.bm), p.splits * S);
-    if (p.bm == 128 && p.bn == 256)
+    if (p.bm == 128 && p.bn == 256) {
+        if (direct_ok(g) && square_tiles_pay(M, cdiv(N, 256), S))
+            return launch_gemm_kernel<256, 256, 2, 1, false, true, 4>(dim3(cdiv(N, 256), cdiv(M, 256), S), g, st);
         return direct_ok(g) ? launch_gemm_kernel<128, 256, 3, 2, false, true>(grid, g, st)
                             : launch_gemm_kernel<128, 256, 2, 2, false>(grid, g, st);
+    }
     if (p.bm == 128) {
         if (!direct_ok(g)) return launch_gemm_kernel<128, 128, 4, 2, false>(grid, g, st);
         // With at least two workgroups per compute unit the two-stage variant (64 KB of LDS, two workgroups
@@ -1227,6 +1283,10 @@ bool launch_gemm_swiglu(const GemmPtrs *ptrs, int S, int lda, int sl, int ldb, i
     g.k_per_split = p.k_per_split; g.splits = 1; g.c_split = 0;
     for (int s = 0; s < S; ++s) g.p[s] = ptrs[s];
     ProfScope ps(kStagePrefillGemm, st);
+    if (p.bn == 256 && direct_ok(g) && square_tiles_pay(M, cdiv(sl, 128), S)) {
+        *err = launch_gemm_kernel<256, 256, 2, 1, true, true, 4>(dim3(cdiv(sl, 128), cdiv(M, 256), S), g, st);
+        return true;
+    }
     if (p.bn == 256) {
         const int cus = std::max(1, current_share()), per_col = cdiv(M, p.bm) * S, cols = cdiv(sl, 128);
         int wide_cols = cols;

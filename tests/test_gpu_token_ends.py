@@ -72,3 +72,20 @@ def test_sampling_frequencies_follow_the_distribution():
         B.tpi_next_token(zt, (i + 0.5) / n, tok)
         counts[int(tok.item())] += 1
     np.testing.assert_allclose(counts / n, O.softmax(z), atol=2.0 / n)
+
+
+@pytest.mark.parametrize("vocab", [1, 5, 1024, 4097])
+def test_greedy_choice_when_no_logit_is_finite(vocab):
+    # every logit -inf: nothing compares greater, so the first index is the answer on both sides and the
+    # token stays inside [0, vocab)
+    z = np.full(vocab, -np.inf, dtype=np.float32)
+    tok = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    B.tpi_next_token(torch.from_numpy(z).cuda(), -1.0, tok)
+    torch.cuda.synchronize()
+    assert int(tok.item()) == O.greedy_token(z) == 0
+    # one finite logit among them is found wherever it lies
+    for at in sorted({0, vocab // 2, vocab - 1}):
+        z2 = z.copy(); z2[at] = -3.0e38
+        B.tpi_next_token(torch.from_numpy(z2).cuda(), -1.0, tok)
+        torch.cuda.synchronize()
+        assert int(tok.item()) == O.greedy_token(z2) == at
