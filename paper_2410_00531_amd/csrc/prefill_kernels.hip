@@ -280,8 +280,10 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
     if constexpr (DIRECT) {
         const int nsteps = span / BK;                   // whole steps (the launcher checks)
         const int w64 = (tid >> 6) * 64;                // this wave's 8 rows of a 64-row slab, in chunks
-        // s_waitcnt immediates: vmcnt in bits 3:0, no wait on the export counter, lgkmcnt 0
-        constexpr int kWaitAll = 0x0070;
+        // s_waitcnt immediates: at most n vector memory loads in flight (bits 3:0 and 15:14), no wait on the export
+        // counter (bits 6:4), every LDS read returned (bits 11:8)
+        auto wait_for_all_but = [](int n) constexpr { return (n & 15) | ((n >> 4) << 14) | 0x0070; };
+        constexpr int kWaitAll = wait_for_all_but(0);
         // One 16-byte-per-lane load from global memory into LDS: the 64 lanes' data go to consecutive LDS addresses
         // starting at `to` (the same for the whole wave; it travels in M0).  Written out as an instruction rather
         // than through the compiler's builtin: the compiler counts such a load as one that may return on either of
@@ -339,8 +341,8 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
         // The last steps request the last step once more (cache hits into a free stage) instead of nothing, so
         // that the count of loads in flight is the same at every wait; the slice read after the last step's
         // barrier comes from such a repeat and is not used.
-        constexpr int kWaitStep = 0x0070 | ((NS - 2) * (ACH + BCH)), kWaitFirst = 0x0070 | ((NS - 1) * (ACH + BCH));
-        static_assert((NS - 1) * (ACH + BCH) <= 15, "the count of loads in flight has four bits in the immediate");
+        constexpr int kWaitStep = wait_for_all_but((NS - 2) * (ACH + BCH)), kWaitFirst = wait_for_all_but((NS - 1) * (ACH + BCH));
+        static_assert((NS - 1) * (ACH + BCH) <= 63, "the count of loads in flight has six bits in the immediate");
         auto direct_step = [&](uint4 *cur, const uint4 *nxt, int t) {
             read_slice(cur, 1, fa1, fb1);
             multiply_slice(fa0, fb0);
