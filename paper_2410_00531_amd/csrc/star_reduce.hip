@@ -24,20 +24,15 @@ __global__ __launch_bounds__(256) void k_star_reduce(ReduceArgs a)
     const int64_t n4 = a.vec_ok ? a.len / 4 : 0;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        // the loads of up to eight ranks (and of the residual) are issued together, the additions follow in rank order
-        float4 res = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (a.residual) res = reinterpret_cast<const float4 *>(a.residual)[i];
         float4 acc = reinterpret_cast<const float4 *>(a.p[0])[i];
-        for (int r0 = 1; r0 < a.n; r0 += 8) {
-            float4 v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (r0 + j < a.n) v[j] = reinterpret_cast<const float4 *>(a.p[r0 + j])[i];
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (r0 + j < a.n) { acc.x = acc.x + v[j].x; acc.y = acc.y + v[j].y; acc.z = acc.z + v[j].z; acc.w = acc.w + v[j].w; }
+        for (int r = 1; r < a.n; ++r) {
+            float4 v = reinterpret_cast<const float4 *>(a.p[r])[i];
+            acc.x = acc.x + v.x; acc.y = acc.y + v.y; acc.z = acc.z + v.z; acc.w = acc.w + v.w;
         }
-        if (a.residual) { acc.x = acc.x + res.x; acc.y = acc.y + res.y; acc.z = acc.z + res.z; acc.w = acc.w + res.w; }
+        if (a.residual) {
+            float4 v = reinterpret_cast<const float4 *>(a.residual)[i];
+            acc.x = acc.x + v.x; acc.y = acc.y + v.y; acc.z = acc.z + v.z; acc.w = acc.w + v.w;
+        }
         reinterpret_cast<float4 *>(a.out)[i] = acc;
         if (a.out_bf16) {
             ushort4 b = make_ushort4(to_bf16(acc.x), to_bf16(acc.y), to_bf16(acc.z), to_bf16(acc.w));

@@ -418,6 +418,21 @@ def test_prefill_two_stage_direct_tiles(h):
         B.tpi_set_prefill_concurrency(1)
 
 
+@pytest.mark.parametrize("h,n", [(2048, 300), (2112, 257)])
+def test_prefill_256x256_tiles_at_a_small_size(h, n):
+    """Products whose 256x256 tiles fill the compute units the call counts on take the eight-wave 256x256 tile (two
+    LDS stages, every wave all four slices of a K-step).  Under the maximum hint that is 16 compute units, which
+    brings the choice to a small shape: 960 hidden units = 8 column tiles of gate|up (the last one half empty) on 2
+    row tiles (the second with 44 rows, or with 1), the down projection with 15 K-steps (one left over after the
+    rounds of two), the output projection with 8, and the QKV product (1024 columns) split 2-way along K over 8
+    tiles: 16 + 16 K-steps at h = 2048, 17 + 16 at h = 2112."""
+    B.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS)
+    try:
+        _run_prefill_case(h, 8, 4, 64, 960, n, 0, n + 1, seed=h + n)
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+
+
 @pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0", [
     (256, 16, 4, 64, 64, 300, 5),      # 4 heads per KV head, non-empty cache, 1200 rows per KV head: a ragged last block
     (512, 8, 1, 128, 64, 530, 0),      # head_dim 128, 8 heads on one KV head, 17 key tiles (rounds of three and two left over)
@@ -436,15 +451,17 @@ def test_prefill_attention_with_tiles_shared_by_128_rows(h, nq, nkv, d, sl, n, p
 
 
 
-def test_prefill_70b_shaped_8_shards_512_tokens_in_one_call():
+@pytest.mark.parametrize("n", [512, 333])
+def test_prefill_70b_shaped_8_shards_in_one_call(n):
     """What the benchmark's prefill leg times, at its real size: tpi_shards_layer_prefill with all 8 shards of a
-    70B-shaped layer and 512 prompt tokens in ONE call per phase (wide tiles, the divided gate|up launch, the
-    3-way split of the QKV product and the shared-tile attention all at once).  Two of the shards are checked
-    element by element against the oracle (about 10 s of CPU each), every shard's cache must have exactly slots
-    0..511 written, and all shards must agree with their own single-shard call within the bf16 tolerance."""
+    70B-shaped layer and the prompt's tokens in ONE call per phase (256x256 tiles for every product, the 3-way split
+    of the QKV product over them and the shared-tile attention all at once); 512 tokens as in the benchmark, and 333,
+    where the second row tile of every product is ragged (77 of 256 rows).  Two of the shards are checked element
+    by element against the oracle (about 10 s of CPU each), every shard's cache must have exactly slots 0..n-1
+    written, and all shards must agree with their own single-shard call within the bf16 tolerance."""
     m = configs.LLAMA2_70B_TP8
     h, nq, nkv, d, sl, N = m.hidden, m.nq_local, m.nkv_local, m.head_dim, m.ffn_local, m.n_shards
-    n, pos0, max_seq = 512, 0, 520
+    pos0, max_seq = 0, n + 8
     cfg = B.make_cfg(h, nq, nkv, d, sl, max_seq, dtype=B.TPI_BF16)
     oc = O.ShardCfg(h, nq, nkv, d, sl, max_seq)
     gen = torch.Generator(device="cuda"); gen.manual_seed(512)
@@ -493,7 +510,7 @@ def test_prefill_70b_shaped_8_shards_512_tokens_in_one_call():
             else:
                 ref = O.ffn_block(oc, w["ffn_norm"], w["w_gate"], w["w_up"], w["w_down"], x)
             e = rel_err(parts[r].cpu().numpy(), ref)
-            print(f"70B-shaped prefill, 8 shards x 512 tokens in one call, shard {r}, phase {phase}: rel err {e:.2e}", flush=True)
+            print(f"70B-shaped prefill, 8 shards x {n} tokens in one call, shard {r}, phase {phase}: rel err {e:.2e}", flush=True)
             assert e <= BF16_TOL, f"shard {r}, phase {phase}: rel err {e:.3e}"
 
 
