@@ -25,13 +25,11 @@ typedef unsigned short bf16_t;   // storage type
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((unsigned)v << 16); }
 
-// round to nearest, ties to even
+// Round to nearest even; NaN stays NaN.  The conversion is the hardware's (two values per instruction where the
+// compiler can pair them), not integer arithmetic on the bits.
 __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+    return __builtin_bit_cast(bf16_t, static_cast<__bf16>(f));
 }
 
 __device__ __forceinline__ float wsum(float v)
