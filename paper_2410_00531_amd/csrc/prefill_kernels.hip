@@ -165,7 +165,12 @@ constexpr int kSwzShift = 1;
 template <int BM, int BN, int NS, int KW, bool SWI = false, bool DIRECT = false, int WM = 2>
 __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
 {
-    static_assert(!SWI || BN % 128 == 0, "the fused activation pairs neighbouring 32-column tiles of a wave");
+    // SWI with a tile whose two wave columns do not hold whole (gate, up) pairs of 32-column tiles (BN = 192): the
+    // left wave column takes the gate rows of the tile's units, the right one their up rows, and the two waves of a
+    // row exchange halves of their accumulators through LDS before the activation.
+    constexpr bool SWI_SPLIT = SWI && BN % 128 != 0;
+    static_assert(!SWI_SPLIT || (DIRECT && KW == 1 && BM / (32 * WM) == 2 && BN % 64 == 0),
+                  "gate and up in different waves: eight waves of two row tiles each, stages as separate arrays");
     static_assert(!DIRECT || NS == 3 || NS == 2, "the direct loads are written for two or three stages");
     static_assert(!DIRECT || KW == 2 || NS == 2, "four waves: two stages, every load waited for in each step");
     constexpr int BK = 64, NT = 128 * WM * KW;          // WM x 2 waves, KW times
@@ -176,7 +181,7 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
     constexpr int STAGE = (BM + BN) * 8;                // chunks per stage
     static_assert(ACH >= 1 && BCH >= 1, "tile too small for the thread count");
     constexpr int NP = NI > 2 ? 2 : NI;                 // column tiles per pass of the accumulator exchange
-    static_assert(NI % NP == 0, "whole passes");
+    static_assert(KW == 1 || NI % NP == 0, "whole passes");
     static_assert(KW == 1 || 8 * NP * 16 * 64 * 4 <= 2 * STAGE * 16, "an exchange pass must fit the LDS stages");
     static_assert(!DIRECT || 8 * 16 * 64 * 4 <= STAGE * 16, "one column tile of an exchange pass per stage");
     extern __shared__ uint4 lds[];                      // 2 * STAGE chunks, sized at launch (not DIRECT)
@@ -226,7 +231,12 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
     }
 #pragma unroll
     for (int i = 0; i < BCH; ++i) {
-        if constexpr (SWI) {
+        if constexpr (SWI_SPLIT) {
+            // tile column -> gate (left wave column) or up (right wave column) row of unit bx * (BN / 2) + ...
+            const int within = (tid + i * NT) >> 3, up = within / (BN / 2);
+            const int unit = min(bx * (BN / 2) + within % (BN / 2), g.n_split - 1);
+            pb[i] = (up ? P.B1 : P.B0) + (size_t)unit * g.ldb;
+        } else if constexpr (SWI) {
             // tile column -> wave half, pair of 32-column tiles (gate, up), unit within the pair
             const int within = (tid + i * NT) >> 3, wh = within / (BN / 2), t32 = (within % (BN / 2)) >> 5;
             const int unit = min(bx * (BN / 2) + wh * (BN / 4) + (t32 >> 1) * 32 + (within & 31), g.n_split - 1);
@@ -516,6 +526,42 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
         }
         if (kh == 0) finish(std::integral_constant<int, 0>{});
         else finish(std::integral_constant<int, 1>{});
+    } else if constexpr (SWI_SPLIT) {
+        // Wave (wm, 0) holds the gate sums of its 64 rows x BN / 2 units, wave (wm, 1) the up sums.  Each hands the
+        // other one of its two row tiles (the left wave its second, the right wave its first) and finishes the row
+        // tile it kept: the stores are shared by all eight waves.  The K loop ended with a barrier: the stages are
+        // free; a wave's slot is NI tiles of 16 x 64 floats, waves 0..3 in the first stage, 4..7 in the second.
+        constexpr int kSlot = NI * 16 * 64;
+        static_assert(4 * kSlot * 4 <= STAGE * 16, "four waves' slots per stage");
+        auto slot_of = [&](int w) { return reinterpret_cast<float *>(w < 4 ? stage_a : stage_b) + (w & 3) * kSlot; };
+        float *mine = slot_of(wave);
+        const float *theirs = slot_of(wave ^ 1);
+        auto hand_over = [&](auto A) {
+            constexpr int a = decltype(A)::value;
+#pragma unroll
+            for (int b = 0; b < NI; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mine[(b * 16 + r) * 64 + lane] = acc[a][b][r];
+        };
+        if (wn == 0) hand_over(std::integral_constant<int, 1>{});
+        else hand_over(std::integral_constant<int, 0>{});
+        __syncthreads();
+        auto activate = [&](auto A) {
+            constexpr int a = decltype(A)::value;       // the row tile this wave kept: gate if a == 0, up if a == 1
+#pragma unroll
+            for (int b = 0; b < NI; ++b) {
+                const int unit = bx * (BN / 2) + b * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wm * (BM / WM) + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const float other = theirs[(b * 16 + r) * 64 + lane];
+                    const float gt = a == 0 ? acc[a][b][r] : other, up = a == 0 ? other : acc[a][b][r];
+                    if (row < g.M && unit < g.n_split) P.act[(size_t)row * g.ldc + unit] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+                }
+            }
+        };
+        if (wn == 0) activate(std::integral_constant<int, 0>{});
+        else activate(std::integral_constant<int, 1>{});
     } else {
         finish(std::integral_constant<int, 0>{});
         if constexpr (MI >= 2) finish(std::integral_constant<int, 1>{});
@@ -1295,7 +1341,28 @@ bool launch_gemm_swiglu(const GemmPtrs *ptrs, int S, int lda, int sl, int ldb, i
     for (int s = 0; s < S; ++s) g.p[s] = ptrs[s];
     ProfScope ps(kStagePrefillGemm, st);
     if (p.bn == 256 && direct_ok(g) && square_tiles_pay(M, cdiv(sl, 128), S)) {
-        *err = launch_gemm_kernel<256, 256, 2, 1, true, true, 4>(dim3(cdiv(sl, 128), cdiv(M, 256), S), g, st);
+        // 256x256 tiles.  When they end with a ragged round and the units of that round divide into exactly one
+        // round of 256x192 tiles (96 units each), the launch is divided: whole rounds of 256x256 tiles, then one
+        // round of the narrower tiles, so that no compute unit idles through a tile's length (70B shape, 8 shards
+        // x 512 tokens: 448 tiles = 256 + 192 become 256 tiles of 128 units + 256 tiles of 96).
+        const int cus = std::max(1, current_share()), per_col = cdiv(M, 256) * S, cols = cdiv(sl, 128);
+        int full_cols = cols;
+        if ((per_col * cols) % cus != 0 && cus % per_col == 0) {
+            const int whole = ((per_col * cols) / cus) * (cus / per_col);       // column tiles of the whole rounds
+            const int rest = sl - whole * 128;
+            if (whole >= 1 && rest > 0 && cdiv(rest, 96) * per_col == cus) full_cols = whole;
+        }
+        const int full_units = std::min(sl, full_cols * 128);
+        g.n_split = full_units; g.N = 2 * full_units;
+        *err = launch_gemm_kernel<256, 256, 2, 1, true, true, 4>(dim3(full_cols, cdiv(M, 256), S), g, st);
+        if (*err != hipSuccess || full_units == sl) return true;
+        g.n_split = sl - full_units; g.N = 2 * g.n_split;
+        for (int s = 0; s < S; ++s) {
+            g.p[s].B0 += (size_t)full_units * ldb;
+            g.p[s].B1 += (size_t)full_units * ldb;
+            g.p[s].act += full_units;
+        }
+        *err = launch_gemm_kernel<256, 192, 2, 1, true, true, 4>(dim3(cdiv(g.n_split, 96), cdiv(M, 256), S), g, st);
         return true;
     }
     if (p.bn == 256) {

@@ -433,6 +433,19 @@ def test_prefill_256x256_tiles_at_a_small_size(h, n):
         B.tpi_set_prefill_concurrency(1)
 
 
+def test_prefill_gate_up_divided_between_256_and_192_column_tiles():
+    """When the 256x256 tiles of gate|up end with a ragged round whose units make exactly one round of 256x192
+    tiles (96 units each; gate sums in the left wave column, up sums in the right one, exchanged through LDS before
+    the activation), the launch is divided.  Under the maximum hint (16 compute units): 300 tokens = 2 row tiles,
+    1720 units = 14 column tiles = 28 tiles; the first 8 column tiles make one whole round, the other 696 units
+    make 8 tiles of 96 (the last with 24 units) on the 2 row tiles = the second round."""
+    B.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS)
+    try:
+        _run_prefill_case(512, 4, 2, 64, 1720, 300, 0, 301, seed=1720)
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+
+
 @pytest.mark.parametrize("h,nq,nkv,d,sl,n,pos0", [
     (256, 16, 4, 64, 64, 300, 5),      # 4 heads per KV head, non-empty cache, 1200 rows per KV head: a ragged last block
     (512, 8, 1, 128, 64, 530, 0),      # head_dim 128, 8 heads on one KV head, 17 key tiles (rounds of three and two left over)
