@@ -433,6 +433,18 @@ def test_prefill_256x256_tiles_at_a_small_size(h, n):
         B.tpi_set_prefill_concurrency(1)
 
 
+@pytest.mark.parametrize("steps", [1, 2, 3, 4, 5])
+def test_prefill_256x256_tiles_with_few_k_steps(steps):
+    """The two-stage loop of the 256x256 tile with 1..5 K-steps of 64 (rounds of two steps, one left over, and the
+    requests that repeat the last step): output projection (K = n_q * 64) and down projection (K = ffn) onto 2048
+    columns, 300 tokens, under the maximum hint (16 tiles = the 16 compute units the call counts on)."""
+    B.tpi_set_prefill_concurrency(B.TPI_MAX_BATCH_SHARDS)
+    try:
+        _run_prefill_case(2048, steps, 1, 64, 64 * steps, 300, 0, 301, seed=70 + steps)
+    finally:
+        B.tpi_set_prefill_concurrency(1)
+
+
 def test_prefill_gate_up_divided_between_256_and_192_column_tiles():
     """When the 256x256 tiles of gate|up end with a ragged round whose units make exactly one round of 256x192
     tiles (96 units each; gate sums in the left wave column, up sums in the right one, exchanged through LDS before
