@@ -70,6 +70,8 @@ def parse():
     ap.add_argument("--window-prefill-layers", type=int, default=16)
     ap.add_argument("--no-handover-probe", action="store_true",
                     help="skip the measurement of what a hand-over between dependent streaming stages costs")
+    ap.add_argument("--no-gemm-probe", action="store_true",
+                    help="skip the measurement of what paces the K loop of the prefill's 256x256 GEMM tile")
     ap.add_argument("--no-config2", action="store_true",
                     help="skip the short leg on the other configuration of the north star (8B-shaped, 4 shards x 32 layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -790,6 +792,25 @@ def handover_probe_leg():
     return out
 
 
+def gemm_loop_probe_leg():
+    """What paces the K loop of the prefill's 256x256 GEMM tile (tpi_probe_gemm_loop): the 8-shard down projection of
+    the 70B shape as the library runs it, and with the loads into LDS, the fragment reads from LDS or the matrix
+    instructions taken out of the kernel, one or two at a time (those variants compute nothing meaningful)."""
+    from paper_2410_00531_amd import binding as B
+    names = {0: "complete_loop", 1: "without_loads", 2: "without_fragment_reads", 4: "without_matrix_instructions",
+             3: "matrix_instructions_only", 5: "fragment_reads_only", 6: "loads_only"}
+    full = B.tpi_probe_gemm_loop(0, reps=10)
+    out = {"workload": "8 shards x [512 x 3584] . [8192 x 3584]^T, bf16, 256x256 tiles",
+           "tflop_per_launch": round(full["tflop_per_launch"], 4), "result_ok": bool(full["result_ok"] == 1),
+           "us_per_launch": {}}
+    for leave_out in (0, 1, 2, 4, 3, 5, 6):
+        r = full if leave_out == 0 else B.tpi_probe_gemm_loop(leave_out, reps=10)
+        out["us_per_launch"][names[leave_out]] = round(r["us_per_launch"], 1)
+    out["tflops_complete_loop"] = round(full["tflops"], 1)
+    out["tflops_matrix_instructions_only"] = round(full["tflop_per_launch"] / (out["us_per_launch"]["matrix_instructions_only"] * 1e-6), 1)
+    return out
+
+
 def config2_leg(args):
     """BASELINE's other configuration (8B-shaped, 4 shards x 32 layers, KV length 512), a short decode leg of its own:
     this script again as a child process, once the big stack has been released; its JSON line is returned in brief."""
@@ -1155,6 +1176,12 @@ def main():
             del blobs, kc, W_all, KV_all, W_one, KV_one
         torch.cuda.empty_cache()
         result["handover_probe"] = handover_probe_leg()
+    # ---- what paces the prefill's GEMM loop -------------------------------------------------------
+    if not args.no_gemm_probe and not args.no_prefill and args.mode == "both":
+        if "blobs" in dir():
+            del blobs, kc, W_all, KV_all, W_one, KV_one
+        torch.cuda.empty_cache()
+        result["gemm_loop_probe"] = gemm_loop_probe_leg()
     # ---- the benchmark spec's other configuration, in brief ------------------------------------------
     if not args.no_config2 and args.mode == "both" and args.workload == "llama2-70b-shaped-tp8":
         if "blobs" in dir():

@@ -541,6 +541,32 @@ typedef struct tpi_probe_result {
 int tpi_probe_handover(uint64_t total_bytes, int32_t segment_kib_per_wave, int32_t mode, int32_t reps,
                        tpi_probe_result *host_out, void *stream);
 
+/*
+ * Measurement aid (not part of the method): what paces the K loop of the
+ * prefill's 256x256 GEMM tile (Sec. 3.1's linear layers at prompt length).
+ * One launch is the down projection of a Llama-2-70B-shaped 8-way shard for a
+ * 512-token prompt, 8 shards per launch ([512 x 3584] . [8192 x 3584]^T,
+ * bf16 in, fp32 out: 512 tiles, 0.24 TFLOP), on buffers the call allocates,
+ * fills with a fixed pseudo-random pattern and frees.  leave_out is a bit mask of the loop's
+ * three activities to take out of the kernel: 1 the loads into LDS after the
+ * first fill of the stages, 2 the fragment reads from LDS, 4 the matrix
+ * instructions (0: the kernel as the library runs it; 7 is not offered).  A
+ * variant with something left out computes nothing meaningful: only its time
+ * is of interest.  us_per_launch: mean over `reps` launches after one untimed
+ * launch; tflops: for leave_out = 0, else 0; result_ok: for leave_out = 0
+ * whether the first and the last output element equal the same sums taken
+ * on the host (1 / 0), -1 otherwise.
+ * Unlike the entry points of the method this call allocates (0.63 GB),
+ * synchronises `stream` and frees again.
+ * TPI_EINVAL: host_out null, leave_out outside [0, 6], reps outside
+ * [1, 1000]; TPI_ERUNTIME: a HIP call failed.
+ */
+typedef struct tpi_gemm_probe_result {
+    double us_per_launch, tflop_per_launch, tflops;
+    int32_t result_ok;
+} tpi_gemm_probe_result;
+int tpi_probe_gemm_loop(int32_t leave_out, int32_t reps, tpi_gemm_probe_result *host_out, void *stream);
+
 const char *tpi_last_error(void);
 
 /* ABI version of this header: bumped when a signature changes. */

@@ -33,7 +33,7 @@ EXPORTED = (
     "tpi_decoder_workspace_bytes", "tpi_decoder_create", "tpi_decoder_token", "tpi_decoder_status",
     "tpi_decoder_grid", "tpi_decoder_destroy",
     "tpi_sim_create", "tpi_sim_stream", "tpi_sim_read", "tpi_sim_run", "tpi_sim_hash", "tpi_sim_destroy",
-    "tpi_sim_set_copy_rate", "tpi_sim_stream_time", "tpi_probe_handover", "tpi_kv_widen", "tpi_window_calibrate",
+    "tpi_sim_set_copy_rate", "tpi_sim_stream_time", "tpi_probe_handover", "tpi_probe_gemm_loop", "tpi_kv_widen", "tpi_window_calibrate",
     "tpi_window_create_blocks_sim", "tpi_window_create_files_sim",
 )
 TPI_STAGE_NONE, TPI_STAGE_QKV, TPI_STAGE_ATTN, TPI_STAGE_OPROJ = 0, 1, 2, 3
@@ -433,6 +433,20 @@ class tpi_probe_result(C.Structure):
     _fields_ = [("us_total", C.c_double), ("tb_per_s", C.c_double), ("us_per_segment", C.c_double),
                 ("segment_mb", C.c_double), ("spread_us", C.c_double), ("chain_us", C.c_double),
                 ("segments", C.c_int32), ("results_ok", C.c_int32), ("gave_up", C.c_int32)]
+
+
+class tpi_gemm_probe_result(C.Structure):
+    _fields_ = [("us_per_launch", C.c_double), ("tflop_per_launch", C.c_double), ("tflops", C.c_double),
+                ("result_ok", C.c_int32)]
+
+
+def tpi_probe_gemm_loop(leave_out: int, reps: int = 5, stream=None) -> dict:
+    l = lib()
+    l.tpi_probe_gemm_loop.restype = C.c_int
+    l.tpi_probe_gemm_loop.argtypes = [C.c_int32, C.c_int32, C.POINTER(tpi_gemm_probe_result), C.c_void_p]
+    r = tpi_gemm_probe_result()
+    _check(l.tpi_probe_gemm_loop(leave_out, reps, C.byref(r), _stream(stream)))
+    return {k: getattr(r, k) for k, _ in tpi_gemm_probe_result._fields_}
 
 
 def tpi_probe_handover(total_bytes: int, segment_kib_per_wave: int, mode: int, reps: int = 3, stream=None) -> dict:

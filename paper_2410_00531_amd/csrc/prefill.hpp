@@ -15,4 +15,7 @@ int prefill_launch(const tpi_shard_cfg *cfg, int n_shards, const tpi_layer_weigh
                    int32_t n_tokens, int phase, const void *h_in, float *const *partial_out, void *const *workspace,
                    hipStream_t stream);
 
+// tpi_probe_gemm_loop: leave_out in [0, 6], reps >= 1 and out non-null are already checked.
+int prefill_probe_gemm_loop(int leave_out, int reps, tpi_gemm_probe_result *out, hipStream_t stream);
+
 }  // namespace tpi

@@ -162,9 +162,12 @@ constexpr int kSwzShift = 1;
 // every load in flight).  Needs whole K-steps (K range a multiple of 64) and the eight-wave tiles.
 // NS = 2 is the same with two stages (step t + 1 requested at the start of step t): half the LDS, so that two
 // workgroups fit a compute unit.
-template <int BM, int BN, int NS, int KW, bool SWI = false, bool DIRECT = false, int WM = 2>
+// LEAVE_OUT is for the loop probe only (tpi_probe_gemm_loop): bit 0 the loads after the first fill of the stages,
+// bit 1 the fragment reads, bit 2 the matrix instructions.  The product kernels are the instantiations with 0.
+template <int BM, int BN, int NS, int KW, bool SWI = false, bool DIRECT = false, int WM = 2, int LEAVE_OUT = 0>
 __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
 {
+    static_assert(LEAVE_OUT == 0 || (DIRECT && !SWI && KW == 1), "the probe variants exist for the direct loop of the plain product");
     // SWI with a tile whose two wave columns do not hold whole (gate, up) pairs of 32-column tiles (BN = 192): the
     // left wave column takes the gate rows of the tile's units, the right one their up rows, and the two waves of a
     // row exchange halves of their accumulators through LDS before the activation.
@@ -229,23 +232,25 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
         int m = min(m0 + ((tid + i * NT) >> 3), g.M - 1);
         pa[i] = P.A + (size_t)m * g.lda;
     }
-#pragma unroll
-    for (int i = 0; i < BCH; ++i) {
+    // row `within` (0 .. BN - 1) of this workgroup's B tile
+    auto b_row_of = [&](int within) -> const bf16_t * {
         if constexpr (SWI_SPLIT) {
             // tile column -> gate (left wave column) or up (right wave column) row of unit bx * (BN / 2) + ...
-            const int within = (tid + i * NT) >> 3, up = within / (BN / 2);
+            const int up = within / (BN / 2);
             const int unit = min(bx * (BN / 2) + within % (BN / 2), g.n_split - 1);
-            pb[i] = (up ? P.B1 : P.B0) + (size_t)unit * g.ldb;
+            return (up ? P.B1 : P.B0) + (size_t)unit * g.ldb;
         } else if constexpr (SWI) {
             // tile column -> wave half, pair of 32-column tiles (gate, up), unit within the pair
-            const int within = (tid + i * NT) >> 3, wh = within / (BN / 2), t32 = (within % (BN / 2)) >> 5;
+            const int wh = within / (BN / 2), t32 = (within % (BN / 2)) >> 5;
             const int unit = min(bx * (BN / 2) + wh * (BN / 4) + (t32 >> 1) * 32 + (within & 31), g.n_split - 1);
-            pb[i] = ((t32 & 1) ? P.B1 : P.B0) + (size_t)unit * g.ldb;
+            return ((t32 & 1) ? P.B1 : P.B0) + (size_t)unit * g.ldb;
         } else {
-            int n = min(n0 + ((tid + i * NT) >> 3), g.N - 1);
-            pb[i] = (n < g.n_split) ? P.B0 + (size_t)n * g.ldb : P.B1 + (size_t)(n - g.n_split) * g.ldb;
+            const int n = min(n0 + within, g.N - 1);
+            return (n < g.n_split) ? P.B0 + (size_t)n * g.ldb : P.B1 + (size_t)(n - g.n_split) * g.ldb;
         }
-    }
+    };
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) pb[i] = b_row_of((tid + i * NT) >> 3);
     // (row * 8 + chunk) -> swizzled LDS position; row & 7 == (tid >> 3) & 7 for every i
     const int st_off = (tid >> 3) * 8 + ((tid & 7) ^ ((tid >> (3 + kSwzShift)) & 7));
 
@@ -306,6 +311,9 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
                          : "=&s"(keep) : "v"(from), "s"(at) : "memory");
         };
         auto request = [&](const uint4 *stage, int t) {
+            if constexpr ((LEAVE_OUT & 1) != 0) {
+                if (t >= NS) { __builtin_amdgcn_sched_barrier(0); return; }
+            }
             int kk = k_begin + t * BK + rot;
             if (kk >= k_end) kk -= span;
             const int ko = kk + kc;
@@ -326,7 +334,14 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
         constexpr int SL = BK / 16 / KW;
         static_assert(SL == 2 || SL == 4, "an even number of slices: the two fragment sets alternate");
         bf16x8 fa0[MI], fb0[NI], fa1[MI], fb1[NI];
+        if constexpr ((LEAVE_OUT & 2) != 0) {       // never read: give the fragments a value
+#pragma unroll
+            for (int a = 0; a < MI; ++a) fa0[a] = fa1[a] = *reinterpret_cast<const bf16x8 *>(P.A + (size_t)lane * 8);
+#pragma unroll
+            for (int b = 0; b < NI; ++b) fb0[b] = fb1[b] = *reinterpret_cast<const bf16x8 *>(P.B0 + (size_t)lane * 8);
+        }
         auto read_slice = [&](const uint4 *base, int s0, bf16x8 (&fa)[MI], bf16x8 (&fb)[NI]) {
+            if constexpr ((LEAVE_OUT & 2) != 0) { __builtin_amdgcn_sched_barrier(0); return; }
             const int ch = (2 * (kh * SL + s0) + hb) ^ sw;
 #pragma unroll
             for (int a = 0; a < MI; ++a) fa[a] = *reinterpret_cast<const bf16x8 *>(base + a_row + a * 32 * 8 + ch);
@@ -338,8 +353,15 @@ __global__ __launch_bounds__(128 * WM * KW) void k_gemm_bf16_nt(GemmArgs g)
 #pragma unroll
             for (int a = 0; a < MI; ++a)
 #pragma unroll
-                for (int b = 0; b < NI; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+                for (int b = 0; b < NI; ++b) {
+                    if constexpr ((LEAVE_OUT & 4) != 0) {   // keep the fragments alive with one addition per product
+                        union { bf16x8 v; float f[4]; } ua, ub;
+                        ua.v = fa[a]; ub.v = fb[b];
+                        acc[a][b][0] += ua.f[0] + ub.f[1] + ua.f[2] + ub.f[3];
+                    } else {
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+                    }
+                }
             __builtin_amdgcn_sched_barrier(0);
         };
         // Step t out of `cur`; its first slice is in fa0 / fb0 already.  Before the barrier this wave's loads of
@@ -1253,13 +1275,13 @@ PrefillLayout layout_of(const tpi_shard_cfg *c, int n)
 }
 
 // Launches one instantiation with its LDS size; above 64 KB the kernel has to opt in once per device.
-template <int BM, int BN, int NS, int KW, bool SWI, bool DIRECT = false, int WM = 2>
+template <int BM, int BN, int NS, int KW, bool SWI, bool DIRECT = false, int WM = 2, int LEAVE_OUT = 0>
 hipError_t launch_gemm_kernel(dim3 grid, const GemmArgs &g, hipStream_t st)
 {
     // DIRECT: the stages are static arrays of the kernel
     constexpr size_t lds = DIRECT ? 0 : (size_t)2 * (BM + BN) * 8 * 16;
     constexpr size_t lds_total = DIRECT ? (size_t)NS * (BM + BN) * 8 * 16 : lds;
-    auto *kern = k_gemm_bf16_nt<BM, BN, NS, KW, SWI, DIRECT, WM>;
+    auto *kern = k_gemm_bf16_nt<BM, BN, NS, KW, SWI, DIRECT, WM, LEAVE_OUT>;
     if constexpr (lds_total > 65536) {
         static std::atomic<bool> opted[64];
         int dev = 0;
@@ -1557,6 +1579,128 @@ int prefill_launch(const tpi_shard_cfg *c, int S, const tpi_layer_weights *w, co
 #undef TPI_LAUNCH_OK
 #undef TPI_GEMM_OK
     return TPI_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Loop probe: the 256x256 tile's K loop with one or two of its three activities left out
+// ---------------------------------------------------------------------------
+namespace {
+
+struct ProbeBuffers {
+    bf16_t *a = nullptr, *b = nullptr;
+    float *c = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ~ProbeBuffers()
+    {
+        if (a) (void)hipFree(a);
+        if (b) (void)hipFree(b);
+        if (c) (void)hipFree(c);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    }
+};
+
+// element i of a probe operand: sign and the low 7 mantissa bits from a hash of i, exponent fixed: +-[2^-7, 2^-6)
+__host__ __device__ inline unsigned short probe_value_bits(size_t i, unsigned salt)
+{
+    unsigned x = (unsigned)i * 2654435761u + salt;
+    x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
+    return (unsigned short)((x & 0x8000u) | 0x3c00u | (x & 0x7fu));
+}
+
+__global__ __launch_bounds__(256) void k_probe_fill_bf16(bf16_t *p, size_t n, unsigned salt)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = probe_value_bits(i, salt);
+}
+
+template <int LEAVE_OUT>
+hipError_t launch_probe_variant(dim3 grid, const GemmArgs &g, hipStream_t st)
+{
+    return launch_gemm_kernel<256, 256, 2, 1, false, true, 4, LEAVE_OUT>(grid, g, st);
+}
+
+}  // namespace
+
+int prefill_probe_gemm_loop(int leave_out, int reps, tpi_gemm_probe_result *out, hipStream_t st)
+{
+#define TPI_PROBE_HIP(call)                                                                          \
+    do {                                                                                             \
+        hipError_t e_ = (call);                                                                      \
+        if (e_ != hipSuccess) return fail(TPI_ERUNTIME, "%s: %s", #call, hipGetErrorString(e_));     \
+    } while (0)
+    // the down projection of the 70B-shaped 8-way shard for a 512-token prompt, 8 shards per launch:
+    // 512 tiles of 256x256 with 56 K-steps each, two rounds of 256 compute units
+    constexpr int S = 8, M = 512, N = 8192, K = 3584;
+    constexpr unsigned kSaltA = 17u, kSaltB = 4099u;
+    const size_t a_elems = (size_t)S * M * K, b_elems = (size_t)S * N * K, c_elems = (size_t)S * M * N;
+    ProbeBuffers B;
+    TPI_PROBE_HIP(hipMalloc(&B.a, a_elems * 2));
+    TPI_PROBE_HIP(hipMalloc(&B.b, b_elems * 2));
+    TPI_PROBE_HIP(hipMalloc(&B.c, c_elems * 4));
+    TPI_PROBE_HIP(hipEventCreate(&B.e0));
+    TPI_PROBE_HIP(hipEventCreate(&B.e1));
+    hipLaunchKernelGGL(k_probe_fill_bf16, dim3(4096), dim3(256), 0, st, B.a, a_elems, kSaltA);
+    hipLaunchKernelGGL(k_probe_fill_bf16, dim3(4096), dim3(256), 0, st, B.b, b_elems, kSaltB);
+    TPI_PROBE_HIP(hipGetLastError());
+    TPI_PROBE_HIP(hipMemsetAsync(B.c, 0, c_elems * 4, st));
+    GemmArgs g{};
+    g.M = M; g.N = N; g.K = K; g.n_split = N; g.lda = K; g.ldb = K; g.ldc = N;
+    g.k_per_split = K; g.splits = 1; g.c_split = (size_t)M * N;
+    for (int s = 0; s < S; ++s) {
+        g.p[s].A = B.a + (size_t)s * M * K;
+        g.p[s].B0 = B.b + (size_t)s * N * K;
+        g.p[s].B1 = g.p[s].B0;
+        g.p[s].C = B.c + (size_t)s * M * N;
+        g.p[s].act = nullptr;
+    }
+    const dim3 grid(N / 256, M / 256, S);
+    auto launch = [&]() -> hipError_t {
+        switch (leave_out) {
+        case 0: return launch_probe_variant<0>(grid, g, st);
+        case 1: return launch_probe_variant<1>(grid, g, st);
+        case 2: return launch_probe_variant<2>(grid, g, st);
+        case 3: return launch_probe_variant<3>(grid, g, st);
+        case 4: return launch_probe_variant<4>(grid, g, st);
+        case 5: return launch_probe_variant<5>(grid, g, st);
+        default: return launch_probe_variant<6>(grid, g, st);
+        }
+    };
+    TPI_PROBE_HIP(launch());                                  // untimed: code load, first touch
+    TPI_PROBE_HIP(hipEventRecord(B.e0, st));
+    for (int r = 0; r < reps; ++r) TPI_PROBE_HIP(launch());
+    TPI_PROBE_HIP(hipEventRecord(B.e1, st));
+    TPI_PROBE_HIP(hipEventSynchronize(B.e1));
+    float ms = 0.f;
+    TPI_PROBE_HIP(hipEventElapsedTime(&ms, B.e0, B.e1));
+    out->us_per_launch = 1e3 * (double)ms / reps;
+    out->tflop_per_launch = 2.0 * S * M * (double)N * K * 1e-12;
+    out->tflops = leave_out == 0 ? out->tflop_per_launch / (out->us_per_launch * 1e-6) : 0.0;
+    // the complete loop must have multiplied: the first and the last output element against the same sums on the host
+    out->result_ok = -1;
+    if (leave_out == 0) {
+        auto value = [](size_t i, unsigned salt) {
+            const unsigned short b = probe_value_bits(i, salt);
+            const double mag = std::ldexp(1.0 + (b & 0x7f) / 128.0, -7);
+            return (b & 0x8000u) ? -mag : mag;
+        };
+        bool ok = true;
+        const size_t where[2][3] = {{0, 0, 0}, {S - 1, M - 1, N - 1}};       // shard, row, column
+        for (const auto &w : where) {
+            double want = 0.0, scale = 0.0;
+            for (int k = 0; k < K; ++k) {
+                const double t = value((w[0] * M + w[1]) * (size_t)K + k, kSaltA) * value((w[0] * N + w[2]) * (size_t)K + k, kSaltB);
+                want += t;
+                scale += std::fabs(t);
+            }
+            float got = 0.f;
+            TPI_PROBE_HIP(hipMemcpy(&got, B.c + (w[0] * M + w[1]) * (size_t)N + w[2], 4, hipMemcpyDeviceToHost));
+            ok = ok && std::fabs(got - want) <= 1e-5 * scale;
+        }
+        out->result_ok = ok ? 1 : 0;
+    }
+    return TPI_OK;
+#undef TPI_PROBE_HIP
 }
 
 }  // namespace tpi

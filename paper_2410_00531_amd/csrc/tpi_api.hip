@@ -350,6 +350,14 @@ int tpi_shards_layer_prefill(const tpi_shard_cfg *cfg, int32_t n_shards, const t
                           stream);
 }
 
+int tpi_probe_gemm_loop(int32_t leave_out, int32_t reps, tpi_gemm_probe_result *host_out, void *stream)
+{
+    if (!host_out) return fail(TPI_EINVAL, "host_out is null");
+    if (leave_out < 0 || leave_out > 6) return fail(TPI_EINVAL, "leave_out %d outside [0, 6]", leave_out);
+    if (reps < 1 || reps > 1000) return fail(TPI_EINVAL, "reps %d outside [1, 1000]", reps);
+    return prefill_probe_gemm_loop(leave_out, reps, host_out, (hipStream_t)stream);
+}
+
 int tpi_set_prefill_concurrency(int32_t n_calls)
 {
     if (n_calls < 1 || n_calls > TPI_MAX_BATCH_SHARDS)
