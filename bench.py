@@ -751,7 +751,7 @@ def prefill_leg(args, m, L, N, seed):
 # "kernel_as_of": the commit whose k_gate_up the counters were read from; a later change to that kernel (stage_gate_up,
 # RowStreamer) makes the figure stale until the two counter runs are repeated.
 MEASURED_GATE_UP_TRAFFIC = {
-    ("llama2-70b-shaped-tp8", 8): {"bytes": 1882007847,   # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB x 1024 from the unrounded averages of that profile
+    ("llama2-70b-shaped-tp8", 8): {"bytes": 1882007848,   # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB x 1024 from the unrounded averages of that profile
                                    "source": "profiles/decode_70b_tp8_eight_shards_per_launch.md",
                                    "kernel_as_of": "6f5c362"},
 }
