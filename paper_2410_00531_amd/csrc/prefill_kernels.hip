@@ -1051,15 +1051,22 @@ __global__ __launch_bounds__(256, 2) void k_prefill_attn_shared(AttnArgs a)
         ld_kc[i] = ((c % CPR) ^ swz_k(ld_row[i])) * 8;
         ld_vc[i] = ((c % CPR) ^ swz_v(ld_row[i])) * 8;
     }
+    // the load into LDS as an instruction, for the reason given in k_gemm_bf16_nt (the compiler's waits for LDS reads
+    // stay exact); the waits these loads need are the explicit ones below
+    auto lds_address = [](const uint4 *p) { return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void *)p; };
+    const unsigned wave_bytes = __builtin_amdgcn_readfirstlane(wave * NLD * 1024);
+    auto load_to_lds = [&](const bf16_t *from, unsigned at) {
+        unsigned keep;      // M0 belongs to the compiler: it is put back before the statement ends
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep) : "v"(from), "s"(at) : "memory");
+    };
     auto request = [&](uint4 *ks, uint4 *vs, int t) {
         const int k0 = t * TK;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
             const size_t key = (size_t)min(k0 + ld_row[i], wg_last_key);     // always in bounds; masked below
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Kg + key * D + ld_kc[i]),
-                                             (__attribute__((address_space(3))) void *)(ks + (wave * NLD + i) * 64), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Vg + key * D + ld_vc[i]),
-                                             (__attribute__((address_space(3))) void *)(vs + (wave * NLD + i) * 64), 16, 0, 0);
+            load_to_lds(Kg + key * D + ld_kc[i], lds_address(ks) + wave_bytes + i * 1024);
+            load_to_lds(Vg + key * D + ld_vc[i], lds_address(vs) + wave_bytes + i * 1024);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
